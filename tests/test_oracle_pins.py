@@ -1,0 +1,417 @@
+"""Pins of the CPU oracle against things other than itself: library routines,
+closed forms, brute force, hand-worked values, the paper's printed sizes -- and a
+mutation check that plants plausible mistakes in the oracle's source (on the CPU)
+and requires that at least one pin notices each of them.
+
+Every pin is a function `pin_*(o)` taking the oracle module, so the same checks
+run against the real module and against the mutants.
+"""
+import importlib.util
+import math
+import os
+import types
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_04857_amd import synth
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ORACLE_PATH = os.path.join(os.path.dirname(HERE), "oracle", "linear_oracle.py")
+
+
+def load_oracle(source=None):
+    if source is None:
+        spec = importlib.util.spec_from_file_location("linear_oracle_pinned", ORACLE_PATH)
+        m = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(m)
+        return m
+    m = types.ModuleType("linear_oracle_mutant")
+    exec(compile(source, "mutant", "exec"), m.__dict__)
+    return m
+
+
+ORACLE = load_oracle()
+
+
+# ----------------------------------------------------------------- helpers ---
+def slice_inputs(w, layer=0, seq=0, head=0):
+    """float64 numpy inputs of one (layer, sequence, head) slice of a workload."""
+    kc, vc = synth.cond_kv(w)
+    q, k, v = synth.image_qkv(w)
+    f = lambda t: t[..., :].to(torch.float64).numpy()
+    return (f(kc[layer, seq, head]), f(vc[layer, seq, head]),
+            f(q[:, layer, seq, head]), f(k[:, layer, seq, head]), f(v[:, layer, seq, head]))
+
+
+def cfg_of(w, **over):
+    c = dict(line_len=w.line_len, n_lines=w.n_lines, budget=w.budget, n_init=w.n_init,
+             n_recent_lines=w.n_recent_lines)
+    c.update(over)
+    return c
+
+
+def sdpa(q, K, V, scale, mask=None):
+    """Library routine: torch's scaled_dot_product_attention on CPU in fp64."""
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))[None]
+    m = None if mask is None else torch.from_numpy(mask)[None]
+    return torch.nn.functional.scaled_dot_product_attention(
+        t(q), t(K), t(V), attn_mask=m, scale=scale)[0].numpy()
+
+
+SMALL = synth.Workload("pin-small", 1, 1, 1, 16, 3, 4, 7, 12, 2, 1, "f32", 9)
+SMALL_R2 = synth.Workload("pin-small-r2", 1, 1, 1, 16, 0, 4, 7, 16, 3, 2, "f32", 10)
+VARIANTS = [synth.shrink(synth.TINY_A, n_heads=1), synth.shrink(synth.TINY_B, n_heads=1),
+            synth.shrink(synth.TINY_C, n_heads=1), SMALL, SMALL_R2]
+
+
+# -------------------------------------------------------------------- pins ---
+def pin_attention_library(o):
+    rng = np.random.default_rng(1)
+    for T, d in [(1, 8), (5, 16), (37, 64)]:
+        q, K, V = rng.normal(size=d), rng.normal(size=(T, d)), rng.normal(size=(T, d + 3))
+        sc = 1.0 / math.sqrt(d)
+        np.testing.assert_allclose(o.attention(q, K, V, sc), sdpa(q[None], K, V, sc)[0],
+                                   rtol=1e-12, atol=1e-13)
+
+
+def pin_attention_closed_forms(o):
+    # logits (ln 3, 0) -> probabilities (3/4, 1/4); scale enters as a factor of the logit.
+    q = np.array([2 * math.log(3.0), 0, 0, 0])
+    K = np.array([[1.0, 0, 0, 0], [0, 5.0, 0, 0]])
+    V = np.array([[1.0, 0.0], [0.0, 1.0]])
+    np.testing.assert_allclose(o.attention(q, K, V, 0.5), [0.75, 0.25], rtol=1e-14)
+    # a single key returns its value row; equal keys return the mean of V.
+    np.testing.assert_allclose(o.attention(q, K[:1], V[:1], 0.5), V[0])
+    Keq = np.tile(np.array([[0.3, -1.0, 2.0, 0.5]]), (6, 1))
+    Vr = np.arange(18.0).reshape(6, 3)
+    np.testing.assert_allclose(o.attention(q, Keq, Vr, 0.5), Vr.mean(0), rtol=1e-14)
+    # large logits must not overflow.
+    big = o.attention(np.array([1e3, 0, 0, 0]), K, V, 1.0)
+    np.testing.assert_allclose(big, [1.0, 0.0], atol=1e-300)
+
+
+def _handworked():
+    rows = []
+    with open(os.path.join(HERE, "golden", "handworked_saliency.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, qs, num, k, ev = [x.strip() for x in line.split("|")]
+            rows.append((name, qs.split(), [int(x) for x in num.split()], int(k),
+                         [int(x) for x in ev.split()]))
+    return rows
+
+
+def pin_saliency_handworked(o):
+    ln2 = math.log(2.0)
+    Kmid = np.array([[0.0, 2.0], [1.0, 1.0], [2.0, 0.0]])
+    qv = {"qa": [ln2, 0.0], "qb": [0.0, ln2]}
+    for name, qs, num, k, ev in _handworked():
+        S = o.saliency(np.array([qv[x] for x in qs]), Kmid, 1.0)
+        np.testing.assert_allclose(S, np.array(num) / 14.0, rtol=1e-14, err_msg=name)
+        # exact rational inputs to the selection, so that the tie really is a tie
+        assert o.bottom_k(np.array(num) / 14.0, k) == ev, name
+
+
+def pin_saliency_invariants(o):
+    rng = np.random.default_rng(2)
+    Q, K = rng.normal(size=(7, 16)), rng.normal(size=(11, 16))
+    S = o.saliency(Q, K, 0.25)
+    assert S.shape == (11,)
+    np.testing.assert_allclose(S.sum(), 1.0, rtol=1e-13)      # every row sums to one
+    Keq = np.tile(rng.normal(size=(1, 16)), (11, 1))
+    np.testing.assert_allclose(o.saliency(Q, Keq, 0.25), np.full(11, 1 / 11), rtol=1e-13)
+    # independent formulation: explicit loops
+    ref = np.zeros(11)
+    for qi in Q:
+        e = np.array([math.exp(0.25 * float(np.dot(qi, kj))) for kj in K])
+        ref += e / e.sum()
+    np.testing.assert_allclose(S, ref / 7, rtol=1e-12)
+
+
+def pin_bottom_k_bruteforce(o):
+    rng = np.random.default_rng(3)
+    for m in (1, 2, 5, 17):
+        for _ in range(20):
+            S = rng.integers(0, 4, size=m).astype(float)        # many exact ties
+            for k in range(0, m + 1):
+                want = sorted(np.argsort(S, kind="stable")[:k].tolist())
+                assert o.bottom_k(S, k) == want
+    assert o.bottom_k(np.array([0.3, 0.1, 0.2]), 1) == [1]
+    assert o.bottom_k(np.array([0.3, 0.1, 0.2]), 2) == [1, 2]
+
+
+def pin_boundary_gap(o):
+    assert o.boundary_gap(np.array([4.0, 1.0, 2.0, 8.0]), 2) == pytest.approx(0.5)   # (4-2)/4
+    assert o.boundary_gap(np.array([1.0, 1.0]), 1) == 0.0
+    assert o.boundary_gap(np.array([1.0, 2.0]), 2) == math.inf
+
+
+def pin_full_budget_is_full_attention(o):
+    """B = N: nothing is evicted and every output is plain causal attention over
+    [cond, visual] (Eq. 2-3), here from the library routine with a causal mask."""
+    for w in (SMALL, synth.shrink(synth.TINY_A, n_heads=1)):
+        kc, vc, Q, K, V = slice_inputs(w)
+        outs, recs, sl = o.run_slice(kc, vc, Q, K, V, **cfg_of(w, budget=w.n_visual))
+        assert recs == [] and sl.visual_len == w.n_visual
+        C, N = w.n_cond, w.n_visual
+        Kall, Vall = np.concatenate([kc, K]), np.concatenate([vc, V])
+        mask = np.zeros((N, C + N), dtype=bool)
+        for i in range(N):
+            mask[i, : C + i + 1] = True
+        ref = sdpa(Q, Kall, Vall, 1.0 / math.sqrt(w.head_dim), mask)
+        np.testing.assert_allclose(outs, ref, rtol=1e-11, atol=1e-12)
+
+
+def pin_masked_full_crosscheck(o):
+    """At every step the compressed-cache output equals attention over the whole
+    history masked to the retained original positions (a second formulation that
+    shares no state with the compacted lists), and compacted rows are exact
+    copies of the rows generated at those positions."""
+    for w in VARIANTS:
+        kc, vc, Q, K, V = slice_inputs(w)
+        Kall, Vall = np.concatenate([kc, K]), np.concatenate([vc, V])
+        sl = o.CacheSlice(kc, vc, **cfg_of(w))
+        sc = 1.0 / math.sqrt(w.head_dim)
+        for i in range(w.n_visual):
+            out = sl.step(Q[i], K[i], V[i])
+            mask = np.zeros((1, len(Kall)), dtype=bool)
+            mask[0, sl.pos] = True
+            np.testing.assert_allclose(out, sdpa(Q[i][None], Kall, Vall, sc, mask)[0],
+                                       rtol=1e-11, atol=1e-12)
+            if sl.pending_eol:
+                sl.end_of_line()
+                pos, Kr, Vr = sl.retained()
+                assert np.array_equal(Kr, Kall[pos]) and np.array_equal(Vr, Vall[pos])
+
+
+def pin_length_trajectory(o):
+    """Visual length grows to B, then saw-tooths B-n+1..B, and is B-n after every
+    eviction (Eq. 6); evictions happen at the ends of lines B/n .. h-1 only."""
+    for w in VARIANTS:
+        kc, vc, Q, K, V = slice_inputs(w)
+        sl = o.CacheSlice(kc, vc, **cfg_of(w))
+        n, B, h = w.line_len, w.budget, w.n_lines
+        evict_lines = []
+        for i in range(1, w.n_visual + 1):
+            sl.step(Q[i - 1], K[i - 1], V[i - 1])
+            want = i if i <= B else B - n + ((i - 1) % n) + 1
+            assert sl.visual_len == want
+            if i % n == 0:
+                r = sl.end_of_line()
+                if r is not None:
+                    evict_lines.append(r["line"])
+                    assert sl.visual_len == B - n and len(r["evicted_positions"]) == n
+        assert evict_lines == list(range(B // n, h))
+
+
+def pin_structure(o):
+    """Retained set always holds the conditional prefix, the first N_init visual
+    tokens and the last r lines; positions ascend; an evicted token never
+    returns; evicted tokens come from the mid region only."""
+    for w in VARIANTS:
+        kc, vc, Q, K, V = slice_inputs(w)
+        sl = o.CacheSlice(kc, vc, **cfg_of(w))
+        C, n, r = w.n_cond, w.line_len, w.n_recent_lines
+        gone = set()
+        for i in range(1, w.n_visual + 1):
+            sl.step(Q[i - 1], K[i - 1], V[i - 1])
+            if i % n:
+                continue
+            rec = sl.end_of_line()
+            pos = sl.pos
+            assert pos == sorted(set(pos))
+            assert set(range(C + min(w.n_init, i))) <= set(pos)
+            assert set(range(C + max(0, i - r * n), C + i)) <= set(pos)
+            assert not (gone & set(pos))
+            if rec is not None:
+                ev = rec["evicted_positions"]
+                assert all(C + w.n_init <= p < C + i - r * n for p in ev)
+                assert set(ev) <= set(rec["mid_positions"])
+                assert len(rec["mid_positions"]) == w.budget - w.n_init - r * n
+                gone |= set(ev)
+                np.testing.assert_allclose(rec["scores"].sum(), 1.0, rtol=1e-12)
+
+
+def pin_sink_plus_window(o):
+    """With mid holding exactly n candidates everything in mid is evicted and the
+    retained set is data-independent: prefix, anchor and the last r lines (the
+    paper's ablation without mid-region tokens, Table 5 row 3, which it scores
+    the same as the Streaming baseline of Table 3)."""
+    w = synth.shrink(synth.TINY_A, n_heads=1)
+    kc, vc, Q, K, V = slice_inputs(w)
+    sl = o.CacheSlice(kc, vc, **cfg_of(w))
+    C, n = w.n_cond, w.line_len
+    for i in range(1, w.n_visual + 1):
+        sl.step(Q[i - 1], K[i - 1], V[i - 1])
+        if i % n == 0:
+            sl.end_of_line()
+            line = i // n
+            if 3 <= line <= w.n_lines - 1:
+                want = list(range(C + n)) + list(range(C + (line - 1) * n, C + line * n))
+                assert sl.pos == want
+
+
+def pin_selection_uses_current_line_queries(o):
+    """Eviction at the end of line l is decided by Eq. 9 on the queries of line l
+    and the keys of the mid region at that moment: recompute it from the raw
+    history and compare the evicted positions, line by line."""
+    for w in (synth.shrink(synth.TINY_B, n_heads=1), synth.shrink(synth.TINY_C, n_heads=1),
+              SMALL_R2):
+        kc, vc, Q, K, V = slice_inputs(w)
+        Kall = np.concatenate([kc, K])
+        outs, recs, sl = o.run_slice(kc, vc, Q, K, V, **cfg_of(w))
+        n, C = w.line_len, w.n_cond
+        sc = 1.0 / math.sqrt(w.head_dim)
+        assert len(recs) == w.n_lines - w.budget // n
+        for r in recs:
+            Qg = Q[(r["line"] - 1) * n: r["line"] * n]
+            Km = Kall[r["mid_positions"]]
+            lg = Qg @ Km.T * sc
+            A = np.exp(lg - lg.max(1, keepdims=True))
+            A /= A.sum(1, keepdims=True)
+            S = A.mean(0)
+            np.testing.assert_allclose(r["scores"], S, rtol=1e-12)
+            order = np.argsort(S, kind="stable")[:n]
+            assert sorted(np.array(r["mid_positions"])[order].tolist()) == r["evicted_positions"]
+
+
+def pin_score_mode_1(o):
+    """score_mode 1: each guide query contributes its decode-time probabilities
+    (softmax over everything it attends to) on the mid tokens."""
+    w = synth.shrink(synth.TINY_C, n_heads=1)
+    kc, vc, Q, K, V = slice_inputs(w)
+    Kall = np.concatenate([kc, K])
+    sl = o.CacheSlice(kc, vc, score_mode=1, **cfg_of(w))
+    n, C = w.line_len, w.n_cond
+    sc = 1.0 / math.sqrt(w.head_dim)
+    acc = None
+    for i in range(1, w.n_visual + 1):
+        visible = list(sl.pos) + [C + i - 1]
+        sl.step(Q[i - 1], K[i - 1], V[i - 1])
+        line = (i - 1) // n + 1
+        if 4 <= line <= w.n_lines - 1:
+            lg = Kall[visible] @ Q[i - 1] * sc
+            p = np.exp(lg - lg.max())
+            p /= p.sum()
+            lo = C + w.n_init
+            hi = C + w.budget - n
+            acc = p[lo:hi] if acc is None else acc + p[lo:hi]
+        if i % n == 0:
+            r = sl.end_of_line()
+            if r is not None:
+                np.testing.assert_allclose(r["scores"], acc / n, rtol=1e-12)
+                assert r["scores"].sum() < 1.0
+                acc = None
+
+
+def pin_table4_budgets(o):
+    """B = rho N as printed in Table 4, and n | B for the line lengths used
+    (24 for N = 576; 49 = 48 + one end-of-line token for N = 2352)."""
+    with open(os.path.join(HERE, "golden", "table4_budgets.txt")) as f:
+        rows = [[int(x) for x in l.split()] for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    for N, a, b, B in rows:
+        assert N * a == B * b
+        n, h = (24, 24) if N == 576 else (49, 48)
+        assert n * h == N and B % n == 0
+        sl = o.CacheSlice(np.zeros((1, 4)), np.zeros((1, 4)), line_len=n, n_lines=h, budget=B,
+                          n_init=n, n_recent_lines=1)
+        assert sl.mid_range() == (1 + n, 1 + B - n)
+    with pytest.raises(ValueError):
+        o.CacheSlice(np.zeros((1, 4)), np.zeros((1, 4)), line_len=48, n_lines=49, budget=294,
+                     n_init=48, n_recent_lines=1)
+    for w in (synth.LLAMAGEN_XL, synth.JANUS_PRO_1B, synth.JANUS_PRO_7B, synth.LUMINA_768):
+        assert (w.n_visual, w.budget) in {(r[0], r[3]) for r in rows}
+
+
+def pin_state_errors(o):
+    w = SMALL
+    kc, vc, Q, K, V = slice_inputs(w)
+    sl = o.CacheSlice(kc, vc, **cfg_of(w))
+    with pytest.raises(RuntimeError):
+        sl.end_of_line()
+    for i in range(w.line_len):
+        sl.step(Q[i], K[i], V[i])
+    with pytest.raises(RuntimeError):
+        sl.step(Q[0], K[0], V[0])
+    with pytest.raises(ValueError):
+        o.CacheSlice(kc, vc, **cfg_of(w, budget=10))
+    with pytest.raises(ValueError):
+        o.CacheSlice(kc, vc, **cfg_of(w, n_init=5))          # 5 + 2*4 > 12
+
+
+def pin_force_evict(o):
+    w = synth.shrink(synth.TINY_C, n_heads=1)
+    kc, vc, Q, K, V = slice_inputs(w)
+    sl = o.CacheSlice(kc, vc, **cfg_of(w))
+    for i in range(4 * w.line_len):
+        sl.step(Q[i], K[i], V[i])
+        if sl.pending_eol and i < 3 * w.line_len:
+            sl.end_of_line()
+    lo, hi = sl.mid_range()
+    forced = sl.pos[lo:hi][-w.line_len:]
+    rec = sl.end_of_line(force_evict_positions=forced)
+    assert rec["forced_positions"] == sorted(forced)
+    assert not (set(forced) & set(sl.pos)) and sl.visual_len == w.budget - w.line_len
+
+
+PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_")]
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
+def test_pin(pin):
+    pin(ORACLE)
+
+
+# -------------------------------------------------------- planted mistakes ---
+MUTANTS = [
+    ("scale dropped in attention", "logits = (np.asarray(K, F) @ np.asarray(q, F)) * scale",
+     "logits = (np.asarray(K, F) @ np.asarray(q, F))"),
+    ("scale dropped in step", "logits = (Kmat @ q) * self.scale", "logits = (Kmat @ q)"),
+    ("no max subtraction", "e = np.exp(x - x.max(axis=axis, keepdims=True))", "e = np.exp(x)"),
+    ("softmax over queries instead of mid tokens", ".T) * scale, axis=1)", ".T) * scale, axis=0)"),
+    ("mean taken over mid instead of queries", "n = A.shape[0]", "n = A.shape[1]"),
+    ("saliency scale dropped", "np.asarray(K_mid, F).T) * scale", "np.asarray(K_mid, F).T)"),
+    ("top-k instead of bottom-k", "key=lambda j: (S[j], j))", "key=lambda j: (-S[j], j))"),
+    ("tie evicts the newer token", "key=lambda j: (S[j], j))", "key=lambda j: (S[j], -j))"),
+    ("first eviction one line late", "self.B // self.n <= line <= self.h - 1",
+     "self.B // self.n < line <= self.h - 1"),
+    ("eviction after the last line", "<= line <= self.h - 1", "<= line <= self.h"),
+    ("mid starts at the prefix", "lo = self.C + self.N_init", "lo = self.C"),
+    ("anchor counted from cache start", "lo = self.C + self.N_init", "lo = self.N_init"),
+    ("recent window one line short", "hi = self.C + self.B - self.r * self.n",
+     "hi = self.C + self.B - (self.r - 1) * self.n"),
+    ("recent window one line long", "hi = self.C + self.B - self.r * self.n",
+     "hi = self.C + self.B - (self.r + 1) * self.n"),
+    ("new token does not attend to itself", "Kmat = np.stack(self.K)\n        Vmat = np.stack(self.V)",
+     "Kmat = np.stack(self.K[:-1] or self.K)\n        Vmat = np.stack(self.V[:-1] or self.V)"),
+    ("K and V swapped on append", "self.K.append(np.asarray(k, F))\n        self.V.append(np.asarray(v, F))",
+     "self.K.append(np.asarray(v, F))\n        self.V.append(np.asarray(k, F))"),
+    ("position off by one", "self.pos.append(self.C + self.i - 1)", "self.pos.append(self.C + self.i)"),
+    ("guide queue never cleared", "self.guide_q, self.guide_p = [], []\n        return rec",
+     "return rec"),
+    ("evicts n-1 tokens", "chosen = bottom_k(S, self.n)", "chosen = bottom_k(S, self.n - 1)"),
+    ("V rows not compacted with K", "self.V = [self.V[j] for j in keep]",
+     "self.V = self.V[:len(keep)]"),
+    ("mode 1 uses mid-only softmax", "self.guide_p.append(p[lo:hi].copy())",
+     "self.guide_p.append(softmax(logits[lo:hi]))"),
+    ("gap uses wrong order statistics", "return float((s[k] - s[k - 1]) / s[k])",
+     "return float((s[k + 1] - s[k]) / s[k + 1])"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(name, old, new):
+    src = open(ORACLE_PATH).read()
+    assert src.count(old) >= 1, f"mutation site for '{name}' not found"
+    mutant = load_oracle(src.replace(old, new))
+    caught = []
+    for pin in PINS:
+        try:
+            pin(mutant)
+        except Exception as e:  # noqa: BLE001 - any failure counts as caught
+            caught.append((pin.__name__, type(e).__name__))
+    assert caught, f"no pin notices: {name}"
