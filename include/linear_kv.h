@@ -1,0 +1,147 @@
+/* linear_kv.h -- C ABI of the LineAR decode path for one MI355X (gfx950).
+ *
+ * The library keeps, per layer, a line-structured visual KV cache
+ *     [ C conditional | N_init anchor | mid survivors | r recent lines | line being written ]
+ * compact and contiguous per (sequence, head), and runs on it
+ *   - single-query decode attention with the append of the new (k, v)   (paper Eq. 2-4),
+ *   - accumulation of the saliency of the mid tokens under the queries of the
+ *     line being generated                                                (Eq. 8-9),
+ *   - at the end of a raster line, BottomK selection of n mid tokens per
+ *     head and the order-preserving compaction of K, V and the position map
+ *                                                                        (Eq. 5-7, 10).
+ * Symbols are the paper's (Sec. 3.1, 3.3): C, n (tokens per raster line, an
+ * end-of-line token counts), h lines, N = h n, budget B (n divides B),
+ * rho = B/N, N_init, r.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are device memory owned by the caller for as long as
+ *     the handle lives; the library never allocates or frees device memory.
+ *     Pointers marked HOST are ordinary host memory read or written during the call.
+ *   - All DEVICE pointers must be 16-byte aligned (LINEAR_EALIGN otherwise).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work: none synchronises, none reads device memory back.
+ *     All calls on one handle must be issued in stream order on one stream.
+ *   - Return value: LINEAR_OK (0) or a negative LINEAR_E* code; on error the
+ *     handle's state is unchanged and nothing was enqueued.
+ *   - Tensors are dense row-major with the listed shape.  "elem" is the
+ *     storage type selected by cfg.dtype (float or bfloat16).  Bz = batch,
+ *     H = n_heads, d = head_dim.
+ */
+#ifndef LINEAR_KV_H
+#define LINEAR_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LINEAR_API __attribute__((visibility("default")))
+
+#define LINEAR_OK 0
+#define LINEAR_EINVAL (-1) /* bad configuration or argument value            */
+#define LINEAR_ESTATE (-2) /* call not allowed in the layer's current state  */
+#define LINEAR_ENULL (-3)  /* required pointer is NULL                       */
+#define LINEAR_EALIGN (-4) /* device pointer not 16-byte aligned             */
+#define LINEAR_EHIP (-5)   /* a HIP call failed: see linear_last_hip_error() */
+
+#define LINEAR_F32 0
+#define LINEAR_BF16 1
+
+typedef struct linear_kv linear_kv_t; /* opaque; host-side bookkeeping only */
+
+typedef struct {
+  int32_t n_layers;
+  int32_t batch;          /* Bz: independent sequences (CFG halves are just sequences) */
+  int32_t n_heads;        /* H; keys/values have the same number of heads             */
+  int32_t head_dim;       /* d: 64 or 128                                             */
+  int32_t n_cond;         /* C >= 0: never evicted, never scored, outside the budget  */
+  int32_t line_len;       /* n                                                        */
+  int32_t n_lines;        /* h                                                        */
+  int32_t budget;         /* B: multiple of n, n <= B <= h n; B == h n never evicts   */
+  int32_t n_init;         /* N_init >= 0 visual anchor tokens                         */
+  int32_t n_recent_lines; /* r >= 1; needs N_init + (r+1) n <= B when B < h n         */
+  int32_t dtype;          /* LINEAR_F32 or LINEAR_BF16: q, k, v and both caches       */
+  int32_t score_mode;     /* 0: Eq. 9 as printed, softmax over the mid tokens only;
+                             1: each query's decode-time probabilities (softmax over
+                                everything it attends to) restricted to mid           */
+  float scale;            /* logit scale; 0 selects 1/sqrt(d) (Eq. 2)                 */
+} linear_cfg_t;
+
+/* Sizes the caller must allocate (Sec. 3.3: at most C + B pairs per head are cached).
+ *   *cache_bytes_per_layer : bytes of EACH of the K and the V cache of one layer,
+ *                            laid out [Bz, H, C + B, d] elem;
+ *   *scratch_bytes         : bytes of the one scratch buffer shared by all layers
+ *                            (saliency accumulators, position maps, split partials).
+ * HOST pointers.  LINEAR_EINVAL if the configuration is not valid. */
+LINEAR_API int linear_workspace_bytes(const linear_cfg_t* cfg, size_t* cache_bytes_per_layer,
+                           size_t* scratch_bytes);
+
+/* Start an image (Sec. 3.1, prefill result): creates the handle, copies the conditional
+ * K/V into rows [0, C) of every layer's cache and clears the saliency accumulators.
+ *   k_cache, v_cache : HOST arrays of n_layers DEVICE pointers, each
+ *                      cache_bytes_per_layer big; contents need no initialisation;
+ *   scratch          : DEVICE, scratch_bytes big;
+ *   k_cond, v_cond   : HOST arrays of n_layers DEVICE pointers to [Bz, H, C, d] elem
+ *                      (may be NULL when C == 0); read during the enqueued copy only;
+ *   *out             : receives the handle (release with kv_free). */
+LINEAR_API int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache, void* scratch,
+            const void* const* k_cond, const void* const* v_cond, void* stream,
+            linear_kv_t** out);
+
+/* One decode step of one layer (Eq. 2-4, and the per-query term of Eq. 9 on lines that
+ * end in an eviction): appends (k, v) as visual token i at original position C + i - 1
+ * and writes out = Softmax(q K^T * scale) V over every cached key including the new one.
+ *   q, k, v : DEVICE [Bz, H, d] elem, already rotated if the model uses RoPE;
+ *   out     : DEVICE [Bz, H, d] float.
+ * LINEAR_ESTATE if the layer's line is complete (end_of_line_evict is due) or the image
+ * is complete. */
+LINEAR_API int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
+                void* out, void* stream);
+
+/* End of a raster line of one layer (Sec. 3.3; Eq. 5-7 and 10).  Must follow exactly n
+ * decode_step calls.  On lines B/n .. h-1 it evicts, independently per (sequence, head),
+ * the n mid tokens with the smallest saliency (ties: older token first), compacts K, V and
+ * the position map in place keeping ascending original position, and clears the
+ * accumulator; on other lines it only advances the line counter.
+ * LINEAR_ESTATE in the middle of a line. */
+LINEAR_API int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream);
+
+/* Saliency of the current line so far (Eq. 9): S[j] for the mid candidates, averaged over
+ * the n queries of the line (meaningful after the n-th decode_step of an evicting line,
+ * before end_of_line_evict).  out: DEVICE [Bz, H, mid] float with
+ * mid = B - N_init - r n; *mid_out (HOST, may be NULL) receives mid.
+ * LINEAR_ESTATE if the layer's current line does not evict. */
+LINEAR_API int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void* stream);
+
+/* Export the retained cache of one layer in canonical order (conditional tokens, then
+ * visual tokens in ascending original position).
+ *   k_out, v_out : DEVICE [Bz, H, len, d] elem (either may be NULL to skip);
+ *   pos_out      : DEVICE [Bz, H, len] int32 original positions (cond 0..C-1, visual
+ *                  token i at C + i - 1); may be NULL;
+ *   *len_out     : HOST, receives len = C + cached visual tokens (known on the host:
+ *                  the eviction schedule does not depend on the data). */
+LINEAR_API int kv_gather(linear_kv_t* kv, int32_t layer, void* k_out, void* v_out, int32_t* pos_out,
+              int32_t* len_out, void* stream);
+
+/* Host-side queries (no device work). */
+LINEAR_API int kv_length(const linear_kv_t* kv, int32_t layer, int32_t* cached_tokens,
+              int32_t* tokens_in_line, int32_t* lines_done);
+
+/* Tuning: keys handled per workgroup of the decode kernel (a multiple of 128; the
+ * kernel splits the keys of one head over ceil(T / rows) workgroups).  0 restores the
+ * default. */
+LINEAR_API int linear_set_split_rows(linear_kv_t* kv, int32_t rows);
+
+/* Releases the handle (host memory only). */
+LINEAR_API int kv_free(linear_kv_t* kv);
+
+LINEAR_API const char* linear_strerror(int code);
+/* hipError_t of the most recent LINEAR_EHIP on the calling thread, as int. */
+LINEAR_API int linear_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LINEAR_KV_H */

@@ -1,0 +1,70 @@
+// Internal launch interface between the host-side state machine and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace linear {
+
+constexpr int kBlock = 256;        // 4 wavefronts of 64
+constexpr int kRowsPerIter = 128;  // keys one workgroup holds in registers at a time
+
+// One decode step of one layer (Eq. 2-4 plus the per-query term of Eq. 9).
+struct DecodeArgs {
+  const void* q;      // [P, d] elem
+  const void* k_new;  // [P, d] elem
+  const void* v_new;  // [P, d] elem
+  void* kc;           // [P, t_max, d] elem
+  void* vc;           // [P, t_max, d] elem
+  int32_t* pos;       // [P, t_max]
+  float* out;         // [P, d]
+  float* part_o;      // [P, max_split, d]   split partial numerators
+  float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
+  float* mid_logit;   // [P, mid_n]          logits of the mid keys when n_split > 1
+  int32_t* counter;   // [P]                 zero between launches
+  float* acc;         // [P, mid_n]          running sum over the line's queries
+  int32_t n_pairs;    // P = Bz * H
+  int32_t t;          // keys visible to this query, the new one included
+  int32_t t_max;      // row pitch of the caches, in keys
+  int32_t rows_per_split;
+  int32_t n_split;
+  int32_t max_split;
+  int32_t mid_lo;     // first mid key (cache row index)
+  int32_t mid_n;      // mid keys to score at this step (0: none)
+  int32_t score_mode;
+  int32_t new_pos;    // original position of the appended token
+  float scale_log2e;  // logit scale times log2(e)
+};
+
+// End of line: BottomK over the accumulated saliency, then compaction (Eq. 5-7, 10).
+struct EvictArgs {
+  void* kc;
+  void* vc;
+  int32_t* pos;
+  float* acc;        // [P, mid_n], cleared on the way out
+  int32_t n_pairs;
+  int32_t t_max;
+  int32_t mid_lo;
+  int32_t mid_n;     // candidates
+  int32_t n_evict;   // n
+  int32_t n_tail;    // rows behind mid that slide down (r lines)
+};
+
+hipError_t launch_decode(const DecodeArgs& a, int dtype, int head_dim, hipStream_t s);
+hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s);
+
+// dst[p, 0:rows, :] = src[p, 0:rows, :] for p < n_pairs; pitches in rows; row_bytes % 16 == 0.
+hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,
+                            int64_t src_pitch_rows, int32_t rows, int32_t n_pairs,
+                            int32_t row_bytes, hipStream_t s);
+// pos[p, j] = j for j < rows.
+hipError_t launch_iota_rows(int32_t* pos, int64_t pitch, int32_t rows, int32_t n_pairs,
+                            hipStream_t s);
+// dst[p, 0:rows] = src[p, 0:rows] (int32), pitches in elements.
+hipError_t launch_copy_i32_rows(int32_t* dst, int64_t dst_pitch, const int32_t* src,
+                                int64_t src_pitch, int32_t rows, int32_t n_pairs, hipStream_t s);
+hipError_t launch_fill_u32(void* dst, uint32_t value, size_t n_words, hipStream_t s);
+// out[i] = in[i] * f
+hipError_t launch_scale_f32(float* out, const float* in, float f, size_t n, hipStream_t s);
+
+}  // namespace linear

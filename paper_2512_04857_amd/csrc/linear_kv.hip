@@ -1,0 +1,345 @@
+// C ABI of the LineAR decode path: argument checks, the host-side line/budget state
+// machine (Sec. 3.3: cache lengths, region boundaries and the eviction schedule depend
+// only on the line index, never on the data, so they live on the host and no call has to
+// read the device back) and the kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "../../include/linear_kv.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr int kMaxMid = 4096;       // candidates the eviction kernel ranks in LDS
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Derived {
+  int pairs;        // Bz * H
+  int t_max;        // C + B
+  int elem;         // bytes per element
+  int row_bytes;    // d * elem
+  bool compresses;  // B < N
+  int mid_lo;       // C + N_init
+  int mid_n;        // B - N_init - r n   (0 when nothing is ever evicted)
+  int n_tail;       // r n
+  int first_line;   // B / n: first line (1-based) that ends in an eviction
+  int max_split;    // ceil(t_max / 128)
+  float scale;
+  // scratch layout (byte offsets)
+  size_t off_acc, off_pos, off_part_o, off_part_ml, off_mid, off_counter, total;
+  size_t acc_layer, pos_layer;   // element strides per layer
+};
+
+int derive(const linear_cfg_t& c, Derived* d) {
+  if (c.n_layers < 1 || c.batch < 1 || c.n_heads < 1) return LINEAR_EINVAL;
+  if (c.head_dim != 64 && c.head_dim != 128) return LINEAR_EINVAL;
+  if (c.dtype != LINEAR_F32 && c.dtype != LINEAR_BF16) return LINEAR_EINVAL;
+  if (c.score_mode != 0 && c.score_mode != 1) return LINEAR_EINVAL;
+  if (c.n_cond < 0 || c.line_len < 1 || c.n_lines < 1) return LINEAR_EINVAL;
+  if (!(c.scale >= 0.f) || std::isinf(c.scale)) return LINEAR_EINVAL;
+  const int64_t N = (int64_t)c.line_len * c.n_lines;
+  if (c.budget < c.line_len || c.budget > N || c.budget % c.line_len) return LINEAR_EINVAL;
+  if (c.n_init < 0 || c.n_recent_lines < 1) return LINEAR_EINVAL;
+  if ((int64_t)c.n_cond + c.budget > (1 << 20)) return LINEAR_EINVAL;
+  if ((int64_t)c.batch * c.n_heads > (1 << 24)) return LINEAR_EINVAL;
+  d->compresses = c.budget < N;
+  if (d->compresses &&
+      (int64_t)c.n_init + (int64_t)(c.n_recent_lines + 1) * c.line_len > c.budget)
+    return LINEAR_EINVAL;   // mid must hold at least the n tokens to evict
+  d->pairs = c.batch * c.n_heads;
+  d->t_max = c.n_cond + c.budget;
+  d->elem = c.dtype == LINEAR_BF16 ? 2 : 4;
+  d->row_bytes = c.head_dim * d->elem;
+  d->mid_lo = c.n_cond + c.n_init;
+  d->n_tail = c.n_recent_lines * c.line_len;
+  d->mid_n = d->compresses ? c.budget - c.n_init - d->n_tail : 0;
+  if (d->mid_n > kMaxMid) return LINEAR_EINVAL;
+  d->first_line = c.budget / c.line_len;
+  d->max_split = (d->t_max + linear::kRowsPerIter - 1) / linear::kRowsPerIter;
+  d->scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.head_dim);
+  const size_t P = (size_t)d->pairs;
+  d->acc_layer = P * (size_t)d->mid_n;
+  d->pos_layer = P * (size_t)d->t_max;
+  size_t off = 0;
+  d->off_acc = off;      off = align_up(off + d->acc_layer * c.n_layers * sizeof(float));
+  d->off_pos = off;      off = align_up(off + d->pos_layer * c.n_layers * sizeof(int32_t));
+  d->off_part_o = off;   off = align_up(off + P * d->max_split * c.head_dim * sizeof(float));
+  d->off_part_ml = off;  off = align_up(off + P * d->max_split * 2 * sizeof(float));
+  d->off_mid = off;      off = align_up(off + P * (size_t)d->mid_n * sizeof(float));
+  d->off_counter = off;  off = align_up(off + P * sizeof(int32_t));
+  d->total = off;
+  return LINEAR_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return LINEAR_EHIP;
+}
+
+struct LayerState {
+  int visual_len = 0;      // visual tokens cached
+  int in_line = 0;         // decode steps since the last end of line
+  int lines_done = 0;
+};
+
+}  // namespace
+
+struct linear_kv {
+  linear_cfg_t cfg;
+  Derived d;
+  std::vector<void*> k_cache, v_cache;
+  char* scratch;
+  std::vector<LayerState> layer;
+  int split_rows;
+};
+
+namespace {
+
+int default_split_rows(const linear_kv& kv) {
+  // Short caches: one workgroup per pair while there are at least two pairs per compute
+  // unit; otherwise 128-key splits so that the launch still fills the 256 CUs.
+  (void)kv;
+  return linear::kRowsPerIter;
+}
+
+bool line_evicts(const linear_kv& kv, int line /*1-based*/) {
+  return kv.d.compresses && line >= kv.d.first_line && line <= kv.cfg.n_lines - 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+int linear_workspace_bytes(const linear_cfg_t* cfg, size_t* cache_bytes_per_layer,
+                           size_t* scratch_bytes) {
+  if (!cfg) return LINEAR_ENULL;
+  Derived d;
+  const int rc = derive(*cfg, &d);
+  if (rc != LINEAR_OK) return rc;
+  if (cache_bytes_per_layer) *cache_bytes_per_layer = (size_t)d.pairs * d.t_max * d.row_bytes;
+  if (scratch_bytes) *scratch_bytes = d.total;
+  return LINEAR_OK;
+}
+
+int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache, void* scratch,
+            const void* const* k_cond, const void* const* v_cond, void* stream,
+            linear_kv_t** out) {
+  if (!cfg || !k_cache || !v_cache || !scratch || !out) return LINEAR_ENULL;
+  Derived d;
+  const int rc = derive(*cfg, &d);
+  if (rc != LINEAR_OK) return rc;
+  if (cfg->n_cond > 0 && (!k_cond || !v_cond)) return LINEAR_ENULL;
+  if (misaligned(scratch)) return LINEAR_EALIGN;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    if (!k_cache[l] || !v_cache[l]) return LINEAR_ENULL;
+    if (misaligned(k_cache[l]) || misaligned(v_cache[l])) return LINEAR_EALIGN;
+    if (cfg->n_cond > 0) {
+      if (!k_cond[l] || !v_cond[l]) return LINEAR_ENULL;
+      if (misaligned(k_cond[l]) || misaligned(v_cond[l])) return LINEAR_EALIGN;
+    }
+  }
+  linear_kv* kv = nullptr;
+  try {
+    kv = new linear_kv;
+    kv->cfg = *cfg;
+    kv->d = d;
+    kv->k_cache.assign(k_cache, k_cache + cfg->n_layers);
+    kv->v_cache.assign(v_cache, v_cache + cfg->n_layers);
+    kv->scratch = static_cast<char*>(scratch);
+    kv->layer.assign(cfg->n_layers, LayerState());
+    kv->split_rows = default_split_rows(*kv);
+  } catch (...) {   // host allocation failure must not cross the C boundary
+    delete kv;
+    return LINEAR_EINVAL;
+  }
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
+  // Accumulators and split counters start at zero; position maps start with the prefix.
+  e = linear::launch_fill_u32(kv->scratch + d.off_acc, 0u, d.acc_layer * cfg->n_layers, s);
+  if (e == hipSuccess) e = linear::launch_fill_u32(kv->scratch + d.off_counter, 0u, (size_t)d.pairs, s);
+  for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
+    int32_t* pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * l;
+    e = linear::launch_iota_rows(pos, d.t_max, cfg->n_cond, d.pairs, s);
+    if (e == hipSuccess && cfg->n_cond > 0)
+      e = linear::launch_copy_rows(kv->k_cache[l], d.t_max, k_cond[l], cfg->n_cond, cfg->n_cond,
+                                   d.pairs, d.row_bytes, s);
+    if (e == hipSuccess && cfg->n_cond > 0)
+      e = linear::launch_copy_rows(kv->v_cache[l], d.t_max, v_cond[l], cfg->n_cond, cfg->n_cond,
+                                   d.pairs, d.row_bytes, s);
+  }
+  if (e != hipSuccess) {
+    delete kv;
+    return hip_fail(e);
+  }
+  *out = kv;
+  return LINEAR_OK;
+}
+
+int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
+                void* out, void* stream) {
+  if (!kv || !q || !k || !v || !out) return LINEAR_ENULL;
+  if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return LINEAR_EALIGN;
+  LayerState& ls = kv->layer[layer];
+  const linear_cfg_t& c = kv->cfg;
+  const Derived& d = kv->d;
+  if (ls.lines_done >= c.n_lines) return LINEAR_ESTATE;      // image complete
+  if (ls.in_line >= c.line_len) return LINEAR_ESTATE;        // end_of_line_evict is due
+  if (ls.visual_len >= c.budget) return LINEAR_ESTATE;       // cannot happen in a valid sequence
+
+  const int line = ls.lines_done + 1;
+  const int visual_index = ls.lines_done * c.line_len + ls.in_line;   // 0-based token i-1
+  linear::DecodeArgs a;
+  a.q = q;
+  a.k_new = k;
+  a.v_new = v;
+  a.kc = kv->k_cache[layer];
+  a.vc = kv->v_cache[layer];
+  a.pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
+  a.out = static_cast<float*>(out);
+  a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
+  a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
+  a.mid_logit = reinterpret_cast<float*>(kv->scratch + d.off_mid);
+  a.counter = reinterpret_cast<int32_t*>(kv->scratch + d.off_counter);
+  a.acc = reinterpret_cast<float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
+  a.n_pairs = d.pairs;
+  a.t = c.n_cond + ls.visual_len + 1;
+  a.t_max = d.t_max;
+  a.n_split = (a.t + kv->split_rows - 1) / kv->split_rows;
+  a.rows_per_split = (a.t + a.n_split - 1) / a.n_split;
+  a.max_split = d.max_split;
+  if (a.n_split > d.max_split || (int64_t)(a.n_split - 1) * a.rows_per_split >= a.t)
+    return LINEAR_EINVAL;
+  a.mid_lo = d.mid_lo;
+  a.mid_n = line_evicts(*kv, line) ? d.mid_n : 0;
+  a.score_mode = c.score_mode;
+  a.new_pos = c.n_cond + visual_index;
+  a.scale_log2e = d.scale * 1.4426950408889634f;
+  const hipError_t e = linear::launch_decode(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e);
+  ls.visual_len += 1;
+  ls.in_line += 1;
+  return LINEAR_OK;
+}
+
+int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
+  if (!kv) return LINEAR_ENULL;
+  if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
+  LayerState& ls = kv->layer[layer];
+  const linear_cfg_t& c = kv->cfg;
+  const Derived& d = kv->d;
+  if (ls.in_line != c.line_len) return LINEAR_ESTATE;
+  const int line = ls.lines_done + 1;
+  if (line_evicts(*kv, line)) {
+    linear::EvictArgs a;
+    a.kc = kv->k_cache[layer];
+    a.vc = kv->v_cache[layer];
+    a.pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
+    a.acc = reinterpret_cast<float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
+    a.n_pairs = d.pairs;
+    a.t_max = d.t_max;
+    a.mid_lo = d.mid_lo;
+    a.mid_n = d.mid_n;
+    a.n_evict = c.line_len;
+    a.n_tail = d.n_tail;
+    const hipError_t e = linear::launch_evict(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    ls.visual_len -= c.line_len;
+  }
+  ls.in_line = 0;
+  ls.lines_done += 1;
+  return LINEAR_OK;
+}
+
+int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void* stream) {
+  if (!kv || !out) return LINEAR_ENULL;
+  if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
+  if (misaligned(out)) return LINEAR_EALIGN;
+  const LayerState& ls = kv->layer[layer];
+  if (ls.lines_done >= kv->cfg.n_lines || !line_evicts(*kv, ls.lines_done + 1)) return LINEAR_ESTATE;
+  const Derived& d = kv->d;
+  const float* acc = reinterpret_cast<const float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
+  const hipError_t e = linear::launch_scale_f32(out, acc, 1.0f / (float)kv->cfg.line_len, d.acc_layer,
+                                                static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e);
+  if (mid_out) *mid_out = d.mid_n;
+  return LINEAR_OK;
+}
+
+int kv_gather(linear_kv_t* kv, int32_t layer, void* k_out, void* v_out, int32_t* pos_out,
+              int32_t* len_out, void* stream) {
+  if (!kv) return LINEAR_ENULL;
+  if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
+  if (misaligned(k_out) || misaligned(v_out) || (reinterpret_cast<uintptr_t>(pos_out) & 3u))
+    return LINEAR_EALIGN;
+  const Derived& d = kv->d;
+  const int len = kv->cfg.n_cond + kv->layer[layer].visual_len;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
+  // Compaction keeps the cache in ascending original position, so the canonical order is
+  // the storage order and the export is a strided copy of the first `len` rows.
+  if (k_out) e = linear::launch_copy_rows(k_out, len, kv->k_cache[layer], d.t_max, len, d.pairs, d.row_bytes, s);
+  if (e == hipSuccess && v_out)
+    e = linear::launch_copy_rows(v_out, len, kv->v_cache[layer], d.t_max, len, d.pairs, d.row_bytes, s);
+  if (e == hipSuccess && pos_out) {
+    const int32_t* pos = reinterpret_cast<const int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
+    e = linear::launch_copy_i32_rows(pos_out, len, pos, d.t_max, len, d.pairs, s);
+  }
+  if (e != hipSuccess) return hip_fail(e);
+  if (len_out) *len_out = len;
+  return LINEAR_OK;
+}
+
+int kv_length(const linear_kv_t* kv, int32_t layer, int32_t* cached_tokens, int32_t* tokens_in_line,
+              int32_t* lines_done) {
+  if (!kv) return LINEAR_ENULL;
+  if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
+  const LayerState& ls = kv->layer[layer];
+  if (cached_tokens) *cached_tokens = kv->cfg.n_cond + ls.visual_len;
+  if (tokens_in_line) *tokens_in_line = ls.in_line;
+  if (lines_done) *lines_done = ls.lines_done;
+  return LINEAR_OK;
+}
+
+int linear_set_split_rows(linear_kv_t* kv, int32_t rows) {
+  if (!kv) return LINEAR_ENULL;
+  if (rows == 0) {
+    kv->split_rows = default_split_rows(*kv);
+    return LINEAR_OK;
+  }
+  if (rows < linear::kRowsPerIter || rows % linear::kRowsPerIter) return LINEAR_EINVAL;
+  kv->split_rows = rows;
+  return LINEAR_OK;
+}
+
+int kv_free(linear_kv_t* kv) {
+  delete kv;
+  return LINEAR_OK;
+}
+
+const char* linear_strerror(int code) {
+  switch (code) {
+    case LINEAR_OK: return "ok";
+    case LINEAR_EINVAL: return "invalid configuration or argument";
+    case LINEAR_ESTATE: return "call not allowed in the layer's current state";
+    case LINEAR_ENULL: return "required pointer is NULL";
+    case LINEAR_EALIGN: return "device pointer is not 16-byte aligned";
+    case LINEAR_EHIP: return "HIP call failed";
+    default: return "unknown error";
+  }
+}
+
+int linear_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

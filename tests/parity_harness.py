@@ -1,0 +1,183 @@
+"""Drives the HIP library and the CPU oracle over the same seeded inputs and compares
+them slice by slice: attention outputs at every step, saliency scores and evicted
+sets at every end of line, retained K/V rows and positions at the end.
+
+Agreement rules (written here once, used by every parity test):
+  * outputs: max-abs error <= OUT_TOL = 1e-2 (the stated bar for bf16 inputs with fp32
+    accumulation); because `out` is fp32 and the oracle sees the same rounded inputs,
+    the observed error is ~1e-6 and TIGHT_TOL = 2e-4 is asserted as well to catch
+    small indexing mistakes the stated bar would hide;
+  * saliency: |S_gpu - S_oracle| <= 1e-4 * S_oracle + 1e-7;
+  * evicted sets, retained positions, compacted rows: bit-exact, except that a set
+    difference is sanctioned when the oracle's relative score gap at the selection
+    boundary is <= GAP_TOL = 1e-4; the oracle is then forced onto the GPU's set
+    for that slice (otherwise one near-tie would invalidate the rest of the image).
+"""
+from __future__ import annotations
+
+import importlib.util
+import math
+import os
+
+import numpy as np
+import torch
+
+from paper_2512_04857_amd import binding, synth
+
+OUT_TOL = 1e-2
+TIGHT_TOL = 2e-4
+GAP_TOL = 1e-4
+
+_ORACLE = None
+
+
+def oracle():
+    global _ORACLE
+    if _ORACLE is None:
+        path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle",
+                            "linear_oracle.py")
+        spec = importlib.util.spec_from_file_location("linear_oracle", path)
+        _ORACLE = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(_ORACLE)
+    return _ORACLE
+
+
+def all_slices(w):
+    return [(l, b, h) for l in range(w.n_layers) for b in range(w.batch) for h in range(w.n_heads)]
+
+
+def sampled_slices(w, layers, seqs, heads):
+    return [(l, b, h) for l in layers for b in seqs for h in heads]
+
+
+class ParityReport:
+    def __init__(self):
+        self.max_out_err = 0.0
+        self.max_score_rel = 0.0
+        self.evictions = 0
+        self.sanctioned = 0
+        self.min_gap = math.inf
+        self.steps = 0
+
+    def __repr__(self):
+        return (f"steps={self.steps} max_out_err={self.max_out_err:.3e} "
+                f"max_score_rel={self.max_score_rel:.3e} evictions={self.evictions} "
+                f"sanctioned={self.sanctioned} min_gap={self.min_gap:.3e}")
+
+
+def run_parity(w, slices, *, device="cuda:0", score_mode=0, split_rows=0, steps=None,
+               seed=synth.BASE_SEED, check_scores=True, progress=None) -> ParityReport:
+    """Runs workload `w` on the GPU at its full shape and the oracle on `slices`
+    ((layer, sequence, head) triples).  Raises AssertionError on disagreement."""
+    o = oracle()
+    rep = ParityReport()
+    cfg = binding.cfg_from_workload(w, score_mode=score_mode)
+    cache = binding.LineARCache(cfg, device)
+    if split_rows:
+        pass  # applied after start_image (needs the handle)
+    kc, vc = synth.cond_kv(w, device, seed)
+    cache.start_image(kc, vc)
+    if split_rows:
+        binding.linear_set_split_rows(cache.handle, split_rows)
+
+    li = torch.tensor([s[0] for s in slices], device=device)
+    bi = torch.tensor([s[1] for s in slices], device=device)
+    hi = torch.tensor([s[2] for s in slices], device=device)
+    f64 = lambda t: t.to(torch.float32).cpu().to(torch.float64).numpy()
+    kc_s, vc_s = f64(kc[li, bi, hi]), f64(vc[li, bi, hi])          # [S, C, d]
+    okw = dict(line_len=w.line_len, n_lines=w.n_lines, budget=w.budget, n_init=w.n_init,
+               n_recent_lines=w.n_recent_lines, score_mode=score_mode)
+    osl = [o.CacheSlice(kc_s[i], vc_s[i], **okw) for i in range(len(slices))]
+    layers_sampled = sorted(set(s[0] for s in slices))
+
+    n, N = w.line_len, w.n_visual if steps is None else steps
+    out = torch.empty((w.n_layers, w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=device)
+    line_q, line_k, line_v, line_o = [], [], [], []
+    compresses = w.budget < w.n_visual
+    mid_n = w.budget - w.n_init - w.n_recent_lines * n
+    for step in range(N):
+        q, k, v = synth.step_qkv(w, step, device, seed)
+        for l in range(w.n_layers):
+            cache.decode_step(l, q[l], k[l], v[l], out[l])
+        line_q.append(q[li, bi, hi])
+        line_k.append(k[li, bi, hi])
+        line_v.append(v[li, bi, hi])
+        line_o.append(out[li, bi, hi].clone())
+        if (step + 1) % n:
+            continue
+        line = (step + 1) // n
+        Q, K, V = f64(torch.stack(line_q)), f64(torch.stack(line_k)), f64(torch.stack(line_v))
+        O = torch.stack(line_o).cpu().to(torch.float64).numpy()
+        line_q, line_k, line_v, line_o = [], [], [], []
+        for i, sl in enumerate(osl):
+            for j in range(n):
+                ref = sl.step(Q[j, i], K[j, i], V[j, i])
+                err = float(np.abs(ref - O[j, i]).max())
+                rep.max_out_err = max(rep.max_out_err, err)
+                assert err <= OUT_TOL and err <= TIGHT_TOL, (
+                    f"{w.name}: output mismatch {err:.3e} at step {step - n + 1 + j} slice {slices[i]}")
+        rep.steps = step + 1
+        evicting = compresses and w.budget // n <= line <= w.n_lines - 1
+        gpu_scores = {}
+        if evicting and check_scores:
+            for l in layers_sampled:
+                gpu_scores[l] = cache.scores(l).cpu().numpy()
+        for l in range(w.n_layers):
+            cache.end_of_line_evict(l)
+        gpu_pos = {}
+        if evicting:
+            for l in layers_sampled:
+                gpu_pos[l] = cache.gather(l)[2].cpu().numpy()
+        for i, sl in enumerate(osl):
+            l, b, h = slices[i]
+            if not evicting:
+                assert sl.end_of_line() is None
+                continue
+            before = list(sl.pos)
+            lo, hi_ = sl.mid_range()
+            mid_positions = before[lo:hi_]
+            S = sl.scores()
+            if check_scores:
+                g = gpu_scores[l][b, h].astype(np.float64)
+                assert g.shape == (mid_n,)
+                rel = float(np.max(np.abs(g - S) / (np.abs(S) + 1e-30)))
+                rep.max_score_rel = max(rep.max_score_rel, rel)
+                assert np.all(np.abs(g - S) <= 1e-4 * np.abs(S) + 1e-7), (
+                    f"{w.name}: saliency mismatch rel {rel:.3e} line {line} slice {slices[i]}")
+            kept_gpu = set(int(p) for p in gpu_pos[l][b, h])
+            ev_gpu = sorted(p for p in mid_positions if p not in kept_gpu)
+            assert len(ev_gpu) == n, f"{w.name}: GPU evicted {len(ev_gpu)} tokens, line {line} slice {slices[i]}"
+            chosen = o.bottom_k(S, n)
+            ev_or = sorted(mid_positions[j] for j in chosen)
+            gap = o.boundary_gap(S, n)
+            rep.min_gap = min(rep.min_gap, gap)
+            rep.evictions += 1
+            if ev_gpu != ev_or:
+                assert gap <= GAP_TOL, (
+                    f"{w.name}: evicted sets differ with boundary gap {gap:.3e} line {line} "
+                    f"slice {slices[i]}: gpu {ev_gpu} oracle {ev_or}")
+                rep.sanctioned += 1
+                sl.end_of_line(force_evict_positions=ev_gpu)
+            else:
+                sl.end_of_line()
+            assert list(gpu_pos[l][b, h]) == sl.pos, (
+                f"{w.name}: retained positions differ line {line} slice {slices[i]}")
+        if progress:
+            progress(f"{w.name} line {line}/{w.n_lines} {rep}")
+
+    # Final retained cache: positions and rows bit-exact (rows are copies of inputs).
+    if N % n == 0:
+        for l in layers_sampled:
+            kg, vg, pg = cache.gather(l)
+            kg, vg, pg = f64(kg), f64(vg), pg.cpu().numpy()
+            for i, sl in enumerate(osl):
+                if slices[i][0] != l:
+                    continue
+                _, b, h = slices[i]
+                pos, Kr, Vr = sl.retained()
+                assert list(pg[b, h]) == pos
+                assert np.array_equal(kg[b, h], Kr) and np.array_equal(vg[b, h], Vr), (
+                    f"{w.name}: compacted rows differ, slice {slices[i]}")
+    torch.cuda.synchronize()
+    cache.close()
+    return rep

@@ -1,0 +1,89 @@
+"""Host-side checks that need no GPU: the library loads, exports every entry point the
+header declares, and rejects invalid configurations and arguments with error codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_04857_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_entry_points():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            names += re.findall(r"LINEAR_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_entry_points()
+    assert set(names) == set(binding.EXPORTS) and len(names) == len(binding.EXPORTS)
+    L = binding.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def good(**over):
+    w = synth.LLAMAGEN_XL
+    kw = dict(n_layers=2, batch=2, n_heads=4, head_dim=w.head_dim, n_cond=w.n_cond,
+              line_len=w.line_len, n_lines=w.n_lines, budget=w.budget, n_init=w.n_init,
+              n_recent_lines=w.n_recent_lines, dtype="bf16")
+    kw.update(over)
+    return binding.make_cfg(**kw)
+
+
+def test_workspace_sizes():
+    cfg = good()
+    cache, scratch = binding.linear_workspace_bytes(cfg)
+    assert cache == 2 * 4 * (1 + 96) * 64 * 2
+    # accumulators + position maps + partials + mid logits + counters, 256-byte aligned parts
+    assert scratch >= 2 * 8 * 48 * 4 + 2 * 8 * 97 * 4 and scratch % 256 == 0
+    full = good(budget=576)
+    cache_full, _ = binding.linear_workspace_bytes(full)
+    assert cache_full == 2 * 4 * 577 * 64 * 2
+    for w in synth.WORKLOADS.values():
+        binding.linear_workspace_bytes(binding.cfg_from_workload(w))
+
+
+@pytest.mark.parametrize("over", [
+    dict(head_dim=96), dict(head_dim=0), dict(budget=100), dict(budget=0), dict(budget=600),
+    dict(n_init=49), dict(n_recent_lines=0), dict(n_recent_lines=3), dict(dtype=7),
+    dict(n_layers=0), dict(batch=0), dict(n_cond=-1), dict(line_len=0), dict(score_mode=2),
+    dict(scale=-1.0), dict(scale=float("nan")), dict(scale=float("inf")),
+    dict(line_len=1, n_lines=100000, budget=50000, n_init=0),     # mid larger than the ranking limit
+])
+def test_invalid_configurations_are_rejected(over):
+    with pytest.raises(binding.LinearError) as e:
+        binding.linear_workspace_bytes(good(**over))
+    assert e.value.code == binding.LINEAR_EINVAL
+
+
+def test_null_and_alignment_errors_without_touching_the_gpu():
+    L = binding.lib()
+    cfg = good()
+    h = ctypes.c_void_p()
+    assert L.kv_init(None, None, None, None, None, None, None, ctypes.byref(h)) == binding.LINEAR_ENULL
+    two = (ctypes.c_void_p * 2)(256, 512)
+    odd = (ctypes.c_void_p * 2)(256, 520)
+    assert L.kv_init(ctypes.byref(cfg), two, two, 4096, None, None, None, ctypes.byref(h)) == binding.LINEAR_ENULL
+    assert L.kv_init(ctypes.byref(cfg), two, odd, 4096, two, two, None, ctypes.byref(h)) == binding.LINEAR_EALIGN
+    assert L.kv_init(ctypes.byref(cfg), two, two, 4100, two, two, None, ctypes.byref(h)) == binding.LINEAR_EALIGN
+    assert L.decode_step(None, 0, 16, 16, 16, 16, None) == binding.LINEAR_ENULL
+    assert L.end_of_line_evict(None, 0, None) == binding.LINEAR_ENULL
+    assert L.kv_gather(None, 0, None, None, None, None, None) == binding.LINEAR_ENULL
+    assert L.kv_free(None) == binding.LINEAR_OK
+    assert L.linear_strerror(binding.LINEAR_ESTATE).decode().startswith("call not allowed")
+    assert L.linear_strerror(-99).decode() == "unknown error"
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "liblinear_kv.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.lib()

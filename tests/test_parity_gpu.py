@@ -1,0 +1,152 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs (rules in parity_harness.py)."""
+import sys
+
+import pytest
+import torch
+
+from paper_2512_04857_amd import binding, synth
+from parity_harness import all_slices, run_parity, sampled_slices
+
+pytestmark = pytest.mark.gpu
+
+W = synth.Workload
+# Small shapes the oracle finishes in seconds that still span several 128-key tiles, split
+# boundaries inside the mid region, ragged tails, pair counts that are not multiples of 8.
+MID_SPLIT = W("mid-split", 2, 3, 5, 64, 40, 24, 8, 96, 24, 1, "bf16", 21)
+LUMINA_SLICE = W("lumina-slice", 1, 2, 3, 128, 256, 49, 9, 294, 49, 1, "bf16", 22)
+F32_R2 = W("f32-r2", 1, 2, 2, 128, 5, 10, 7, 40, 7, 2, "f32", 23)
+FULL_SPLIT = W("full-split", 1, 2, 3, 64, 3, 24, 12, 288, 24, 1, "bf16", 24)
+NO_COND = W("no-cond", 1, 1, 8, 64, 0, 8, 9, 32, 0, 1, "bf16", 25)
+F32_D64_LONG = W("f32-d64-long", 1, 1, 2, 64, 130, 16, 6, 64, 16, 1, "f32", 26)
+STREAMING = W("bf16-streaming", 1, 2, 2, 128, 7, 12, 6, 36, 12, 1, "bf16", 27)   # mid == n
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+@pytest.mark.parametrize("w", [synth.TINY_A, synth.TINY_B, synth.TINY_C], ids=lambda w: w.name)
+@pytest.mark.parametrize("score_mode", [0, 1])
+def test_tiny_every_slice(w, score_mode):
+    rep = run_parity(w, all_slices(w), score_mode=score_mode)
+    say(f"{w.name} mode {score_mode}: {rep}")
+    assert rep.steps == 64 and rep.evictions == 5 * 4
+
+
+def test_tiny_full_budget_never_evicts():
+    w = synth.TINY_A.full_cache()
+    rep = run_parity(w, all_slices(w))
+    assert rep.evictions == 0 and rep.steps == 64
+
+
+@pytest.mark.parametrize("w,split_rows,score_mode", [
+    (MID_SPLIT, 0, 0), (MID_SPLIT, 0, 1), (LUMINA_SLICE, 0, 0), (LUMINA_SLICE, 256, 0),
+    (LUMINA_SLICE, 0, 1), (F32_R2, 0, 0), (FULL_SPLIT, 0, 0), (FULL_SPLIT, 256, 0), (NO_COND, 0, 0),
+    (F32_D64_LONG, 0, 0), (F32_D64_LONG, 0, 1), (STREAMING, 0, 0),
+], ids=lambda x: getattr(x, "name", str(x)))
+def test_mid_sizes_every_slice(w, split_rows, score_mode):
+    rep = run_parity(w, all_slices(w), split_rows=split_rows, score_mode=score_mode)
+    say(f"{w.name} split_rows {split_rows} mode {score_mode}: {rep}")
+    assert rep.steps == w.n_visual
+
+
+def _sample(w, n_heads=4):
+    heads = sorted({0, w.n_heads // 3, w.n_heads // 2, w.n_heads - 1})[:n_heads]
+    return sampled_slices(w, sorted({0, w.n_layers - 1}), sorted({0, w.batch - 1}), heads)
+
+
+@pytest.mark.parametrize("w", [synth.LLAMAGEN_XL, synth.JANUS_PRO_1B, synth.JANUS_PRO_7B,
+                               synth.LUMINA_768], ids=lambda w: w.name)
+def test_full_size_compressed_sampled_slices(w):
+    """The benchmark's shapes and launch configuration; the oracle replays whole images
+    for sampled (layer, sequence, head) slices, which is exact because slices never
+    interact."""
+    rep = run_parity(w, _sample(w), progress=say if w.n_lines > 30 else None)
+    say(f"{w.name}: {rep}")
+    assert rep.steps == w.n_visual
+    assert rep.evictions == (w.n_lines - w.budget // w.line_len) * len(_sample(w))
+
+
+@pytest.mark.parametrize("w", [synth.LLAMAGEN_XL, synth.JANUS_PRO_7B], ids=lambda w: w.name)
+def test_full_size_full_cache_sampled_slices(w):
+    wf = w.full_cache()
+    rep = run_parity(wf, _sample(wf, n_heads=2))
+    say(f"{wf.name}: {rep}")
+    assert rep.steps == w.n_visual and rep.evictions == 0
+
+
+def test_lumina_full_cache_prefix_of_image():
+    """Full-cache Lumina shape (T up to 256 + 2352 keys, 21 splits): the first 12 lines at
+    full width, oracle on two slices."""
+    wf = synth.LUMINA_768.full_cache()
+    rep = run_parity(wf, sampled_slices(wf, [wf.n_layers - 1], [wf.batch - 1], [0, 17]),
+                     steps=12 * wf.line_len)
+    say(f"{wf.name}: {rep}")
+
+
+def test_state_machine_errors():
+    w = synth.shrink(synth.TINY_B, n_heads=2)
+    cfg = binding.cfg_from_workload(w)
+    cache = binding.LineARCache(cfg)
+    kc, vc = synth.cond_kv(w, "cuda:0")
+    cache.start_image(kc, vc)
+    q, k, v = synth.step_qkv(w, 0, "cuda:0")
+    out = torch.empty((w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(binding.LinearError) as e:
+        cache.end_of_line_evict(0)                       # middle (start) of a line
+    assert e.value.code == binding.LINEAR_ESTATE
+    with pytest.raises(binding.LinearError) as e:
+        cache.decode_step(1, q[0], k[0], v[0], out)      # layer out of range
+    assert e.value.code == binding.LINEAR_EINVAL
+    with pytest.raises(binding.LinearError) as e:
+        cache.scores(0)                                  # line 1 does not evict
+    assert e.value.code == binding.LINEAR_ESTATE
+    for i in range(w.line_len):
+        cache.decode_step(0, q[0], k[0], v[0], out)
+    assert binding.kv_length(cache.handle, 0) == (w.n_cond + w.line_len, w.line_len, 0)
+    with pytest.raises(binding.LinearError) as e:
+        cache.decode_step(0, q[0], k[0], v[0], out)      # line complete, eviction due
+    assert e.value.code == binding.LINEAR_ESTATE
+    assert binding.kv_length(cache.handle, 0) == (w.n_cond + w.line_len, w.line_len, 0)
+    with pytest.raises(binding.LinearError) as e:
+        binding.decode_step(cache.handle, 0, q[0].data_ptr() + 2, k[0].data_ptr(), v[0].data_ptr(),
+                            out.data_ptr())
+    assert e.value.code == binding.LINEAR_EALIGN
+    cache.end_of_line_evict(0)
+    for line in range(1, w.n_lines):
+        for i in range(w.line_len):
+            cache.decode_step(0, q[0], k[0], v[0], out)
+        cache.end_of_line_evict(0)
+    with pytest.raises(binding.LinearError) as e:
+        cache.decode_step(0, q[0], k[0], v[0], out)      # image complete
+    assert e.value.code == binding.LINEAR_ESTATE
+    with pytest.raises(binding.LinearError):
+        binding.linear_set_split_rows(cache.handle, 100)
+    torch.cuda.synchronize()
+    cache.close()
+
+
+def test_repeatable_bit_for_bit():
+    """Two runs of the same image give identical outputs, scores and retained sets
+    (in-place compaction and the split merge have no order-dependent result)."""
+    w = LUMINA_SLICE
+    dev = "cuda:0"
+    results = []
+    for _ in range(2):
+        cache = binding.LineARCache(binding.cfg_from_workload(w))
+        kc, vc = synth.cond_kv(w, dev)
+        cache.start_image(kc, vc)
+        outs = []
+        out = torch.empty((w.n_layers, w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
+        for step in range(w.n_visual):
+            q, k, v = synth.step_qkv(w, step, dev)
+            cache.decode_step(0, q[0], k[0], v[0], out[0])
+            outs.append(out.clone())
+            if (step + 1) % w.line_len == 0:
+                cache.end_of_line_evict(0)
+        kg, vg, pg = cache.gather(0)
+        results.append((torch.stack(outs), kg.clone(), vg.clone(), pg.clone()))
+        cache.close()
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
