@@ -31,7 +31,7 @@ def say(msg):
 def test_tiny_every_slice(w, score_mode):
     rep = run_parity(w, all_slices(w), score_mode=score_mode)
     say(f"{w.name} mode {score_mode}: {rep}")
-    assert rep.steps == 64 and rep.evictions == 5 * 4
+    assert rep.steps == 64 and rep.evictions == (w.n_lines - w.budget // w.line_len) * w.n_heads
 
 
 def test_tiny_full_budget_never_evicts():
