@@ -43,8 +43,8 @@ def cpu_baseline(w, budget_s: float):
     spec = importlib.util.spec_from_file_location("linear_oracle", os.path.join(ROOT, "oracle", "linear_oracle.py"))
     o = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(o)
-    n_slices = min(w.n_heads, 8)
-    ws = synth.shrink(w, n_layers=1, batch=1, n_heads=n_slices)
+    n_heads = min(w.n_heads, 8)
+    ws = synth.shrink(w, n_layers=1, batch=1, n_heads=n_heads)
     torch.set_num_threads(1)
     kc, vc = synth.cond_kv(ws)
     q, k, v = synth.image_qkv(ws)
@@ -52,18 +52,17 @@ def cpu_baseline(w, budget_s: float):
     kc, vc, q, k, v = f(kc[0, 0]), f(vc[0, 0]), f(q[:, 0, 0]), f(k[:, 0, 0]), f(v[:, 0, 0])
     done, t0 = 0, time.perf_counter()
     with threadpool_limits(limits=1):
-        for h in range(n_slices):
+        while time.perf_counter() - t0 < budget_s:      # whole images only; heads taken in turn
+            h = done % n_heads
             o.run_slice(kc[h], vc[h], q[:, h], k[:, h], v[:, h], line_len=w.line_len, n_lines=w.n_lines,
                         budget=w.budget, n_init=w.n_init, n_recent_lines=w.n_recent_lines)
             done += 1
-            if time.perf_counter() - t0 > budget_s:
-                break
     dt = time.perf_counter() - t0
     total_slices = w.n_layers * w.batch * w.n_heads
     us_per_step = dt / (done * w.n_visual) * total_slices * 1e6
     return {"value": round(us_per_step, 1), "unit": "us/step", "cores": 1, "kind": "oracle",
-            "sample": f"{done} of {total_slices} (layer, sequence, head) slices x all {w.n_visual} steps of one "
-                      f"image in {dt:.1f} s, scaled linearly to all slices"}
+            "sample": f"{done} whole-image replays ({w.n_visual} steps each) of single (layer, sequence, head) "
+                      f"slices in {dt:.1f} s, scaled linearly to the workload's {total_slices} slices"}
 
 
 def sum_keys(w, steps):
@@ -96,14 +95,14 @@ class Runner:
         self.stride = self.q[0, 0].numel() * self.q.element_size()
         self.ostride = self.out[0].numel() * 4
 
-    def run(self, wl, steps, warmup, split_rows=0):
+    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0):
         """Times `steps` decode steps of workload variant `wl` (same shapes, its own budget)
         from the start of an image.  Returns a dict of measurements."""
         torch, binding = self.torch, self.binding
         L, n = wl.n_layers, wl.line_len
         cache = binding.LineARCache(binding.cfg_from_workload(wl), self.device)
         lib = binding.lib()
-        dstep, evict = lib.decode_step, lib.end_of_line_evict
+        dsteps, evicts = lib.decode_step_layers, lib.end_of_line_evict_layers
         qb, kb, vb, ob = self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(), self.out.data_ptr()
         st, ost = self.stride, self.ostride
         stream = cache.stream()
@@ -111,28 +110,25 @@ class Runner:
         def image(n_steps, events):
             cache.start_image(self.kc, self.vc)
             h = cache.handle
-            if split_rows:
-                binding.linear_set_split_rows(h, split_rows)
+            if groups_per_wave or n_split:
+                binding.linear_set_tuning(h, groups_per_wave, n_split)
             if events is not None:
                 torch.cuda.synchronize()
                 events.append(("start", torch.cuda.Event(enable_timing=True)))
                 events[-1][1].record()
             for s in range(n_steps):
-                base = s * L * st
-                for l in range(L):
-                    off = base + l * st
-                    rc = dstep(h, l, qb + off, kb + off, vb + off, ob + l * ost, stream)
-                    if rc:
-                        raise binding.LinearError(rc, "decode_step")
+                off = s * L * st
+                rc = dsteps(h, 0, L, qb + off, kb + off, vb + off, ob, st, ost, stream)
+                if rc:
+                    raise binding.LinearError(rc, "decode_step_layers")
                 if (s + 1) % n == 0:
                     if events is not None:
                         e = torch.cuda.Event(enable_timing=True)
                         e.record()
                         events.append(("decode_end", e))
-                    for l in range(L):
-                        rc = evict(h, l, stream)
-                        if rc:
-                            raise binding.LinearError(rc, "end_of_line_evict")
+                    rc = evicts(h, 0, L, stream)
+                    if rc:
+                        raise binding.LinearError(rc, "end_of_line_evict_layers")
                     if events is not None:
                         e = torch.cuda.Event(enable_timing=True)
                         e.record()
@@ -141,6 +137,7 @@ class Runner:
                 e = torch.cuda.Event(enable_timing=True)
                 e.record()
                 events.append(("stop", e))
+                self.enqueue_s = time.perf_counter()
                 torch.cuda.synchronize()
 
         image(min(warmup, wl.n_visual), None)
@@ -149,6 +146,7 @@ class Runner:
         t0 = time.perf_counter()
         image(steps, ev)
         wall = time.perf_counter() - t0
+        enqueue = self.enqueue_s - t0
         cache.close()
 
         total_ms = ev[0][1].elapsed_time(ev[-1][1])
@@ -182,6 +180,7 @@ class Runner:
             "us_per_step": total_ms * 1e3 / steps,
             "total_ms": total_ms,
             "host_wall_ms": wall * 1e3,
+            "host_enqueue_ms": enqueue * 1e3,
             "decode_ms": decode_ms,
             "evict_ms": evict_ms,
             "us_per_step_first_half": first,
@@ -193,6 +192,7 @@ class Runner:
             "kv_bytes_per_launch": keys * tok_bytes / steps,
             "kv_bytes_total": keys * tok_bytes * L,
             "mean_keys": keys / steps,
+            "line_us_per_launch": [round(x * 1e3 / (n * L), 2) for x in line_ms],
         }
 
 
@@ -217,7 +217,8 @@ def main():
     ap.add_argument("--workload", default="llamagen-xl")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="0 skips the CPU oracle leg")
     ap.add_argument("--skip-full", action="store_true", help="do not time the full-cache variant")
-    ap.add_argument("--split-rows", type=int, default=0)
+    ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
+    ap.add_argument("--n-split", type=int, default=0, help="decode kernel tuning (0 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -243,9 +244,9 @@ def main():
         return 3
     device = "cuda:0"
     r = Runner(w, device)
-    comp = r.run(w, steps, args.warmup, args.split_rows)
+    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split)
     log("compressed:", json.dumps(comp))
-    full = None if args.skip_full else r.run(w.full_cache(), steps, args.warmup, args.split_rows)
+    full = None if args.skip_full else r.run(w.full_cache(), steps, args.warmup, args.groups_per_wave, args.n_split)
     if full:
         log("full cache:", json.dumps(full))
 
@@ -266,8 +267,8 @@ def main():
         "config": {"workload": w.name, "n_layers": w.n_layers, "sequences": w.batch, "n_heads": w.n_heads,
                    "head_dim": w.head_dim, "n_cond": w.n_cond, "grid": f"{w.n_lines}x{w.line_len}",
                    "budget": w.budget, "n_init": w.n_init, "n_recent_lines": w.n_recent_lines,
-                   "launches": "one decode_step per layer per token, one end_of_line_evict per layer per line, "
-                               "single stream, no graph"},
+                   "launches": "one decode kernel per layer per token, one eviction kernel per layer per line, "
+                               "enqueued back to back on one stream (decode_step_layers), no graph"},
         "whole_image_ms": round(comp["total_ms"], 3) if steps == w.n_visual else None,
         "us_per_step_first_half": comp["us_per_step_first_half"],
         "us_per_step_last_half": comp["us_per_step_last_half"],

@@ -100,6 +100,15 @@ LINEAR_API int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* cons
 LINEAR_API int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
                 void* out, void* stream);
 
+/* The same step for `count` consecutive layers whose inputs are already resident (a
+ * benchmark, or a runtime that pipelines layers): exactly decode_step(kv, first_layer + i,
+ * q + i*qkv_stride, k + i*qkv_stride, v + i*qkv_stride, out + i*out_stride, stream) for
+ * i = 0 .. count-1 (strides in bytes, multiples of 16), enqueued back to back.  Stops at the
+ * first error and returns it; layers before it have been enqueued and advanced. */
+LINEAR_API int decode_step_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, const void* q,
+                       const void* k, const void* v, void* out, size_t qkv_stride,
+                       size_t out_stride, void* stream);
+
 /* End of a raster line of one layer (Sec. 3.3; Eq. 5-7 and 10).  Must follow exactly n
  * decode_step calls.  On lines B/n .. h-1 it evicts, independently per (sequence, head),
  * the n mid tokens with the smallest saliency (ties: older token first), compacts K, V and
@@ -107,6 +116,9 @@ LINEAR_API int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const 
  * accumulator; on other lines it only advances the line counter.
  * LINEAR_ESTATE in the middle of a line. */
 LINEAR_API int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream);
+
+/* end_of_line_evict for layers first_layer .. first_layer + count - 1, enqueued back to back. */
+LINEAR_API int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, void* stream);
 
 /* Saliency of the current line so far (Eq. 9): S[j] for the mid candidates, averaged over
  * the n queries of the line (meaningful after the n-th decode_step of an evicting line,
@@ -129,10 +141,14 @@ LINEAR_API int kv_gather(linear_kv_t* kv, int32_t layer, void* k_out, void* v_ou
 LINEAR_API int kv_length(const linear_kv_t* kv, int32_t layer, int32_t* cached_tokens,
               int32_t* tokens_in_line, int32_t* lines_done);
 
-/* Tuning: keys handled per workgroup of the decode kernel (a multiple of 128; the
- * kernel splits the keys of one head over ceil(T / rows) workgroups).  0 restores the
- * default. */
-LINEAR_API int linear_set_split_rows(linear_kv_t* kv, int32_t rows);
+/* Tuning of the decode kernel's launch shape (defaults are chosen per configuration).
+ *   groups_per_wave : 1..16 row groups (one wave-wide 1 KiB load each) a wavefront should
+ *                     take; fewer groups per wavefront = more wavefronts per pair; 0 = default;
+ *   n_split         : workgroups the keys of one pair are split over, 1..64 (a split step
+ *                     is two launches: partials, then merge); lowered for steps with too
+ *                     few keys to give every workgroup one; 0 = automatic.
+ * A shape that cannot hold a step's keys makes that decode_step return LINEAR_EINVAL. */
+LINEAR_API int linear_set_tuning(linear_kv_t* kv, int32_t groups_per_wave, int32_t n_split);
 
 /* Releases the handle (host memory only). */
 LINEAR_API int kv_free(linear_kv_t* kv);

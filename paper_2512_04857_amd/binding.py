@@ -16,8 +16,9 @@ LIB_PATH = os.path.join(_HERE, "liblinear_kv.so")
 LINEAR_OK, LINEAR_EINVAL, LINEAR_ESTATE, LINEAR_ENULL, LINEAR_EALIGN, LINEAR_EHIP = 0, -1, -2, -3, -4, -5
 LINEAR_F32, LINEAR_BF16 = 0, 1
 
-EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "end_of_line_evict", "kv_scores",
-           "kv_gather", "kv_length", "linear_set_split_rows", "kv_free", "linear_strerror",
+EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_layers",
+           "end_of_line_evict", "end_of_line_evict_layers", "kv_scores",
+           "kv_gather", "kv_length", "linear_set_tuning", "kv_free", "linear_strerror",
            "linear_last_hip_error")
 
 
@@ -54,11 +55,13 @@ def lib() -> C.CDLL:
         L.kv_init.argtypes = [C.POINTER(LinearCfg), C.POINTER(vp), C.POINTER(vp), vp, C.POINTER(vp),
                               C.POINTER(vp), vp, C.POINTER(vp)]
         L.decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.decode_step_layers.argtypes = [vp, i32, i32, vp, vp, vp, vp, C.c_size_t, C.c_size_t, vp]
         L.end_of_line_evict.argtypes = [vp, i32, vp]
+        L.end_of_line_evict_layers.argtypes = [vp, i32, i32, vp]
         L.kv_scores.argtypes = [vp, i32, vp, C.POINTER(i32), vp]
         L.kv_gather.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
         L.kv_length.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
-        L.linear_set_split_rows.argtypes = [vp, i32]
+        L.linear_set_tuning.argtypes = [vp, i32, i32]
         L.kv_free.argtypes = [vp]
         L.linear_strerror.argtypes = [C.c_int]
         L.linear_strerror.restype = C.c_char_p
@@ -115,6 +118,19 @@ def decode_step(kv: int, layer: int, q: int, k: int, v: int, out: int, stream: i
         raise LinearError(rc, "decode_step")
 
 
+def decode_step_layers(kv: int, first_layer: int, count: int, q: int, k: int, v: int, out: int,
+                       qkv_stride: int, out_stride: int, stream: int = 0) -> None:
+    rc = lib().decode_step_layers(kv, first_layer, count, q, k, v, out, qkv_stride, out_stride, stream)
+    if rc:
+        raise LinearError(rc, "decode_step_layers")
+
+
+def end_of_line_evict_layers(kv: int, first_layer: int, count: int, stream: int = 0) -> None:
+    rc = lib().end_of_line_evict_layers(kv, first_layer, count, stream)
+    if rc:
+        raise LinearError(rc, "end_of_line_evict_layers")
+
+
 def end_of_line_evict(kv: int, layer: int, stream: int = 0) -> None:
     rc = lib().end_of_line_evict(kv, layer, stream)
     if rc:
@@ -139,8 +155,8 @@ def kv_length(kv: int, layer: int) -> tuple[int, int, int]:
     return a.value, b.value, c.value
 
 
-def linear_set_split_rows(kv: int, rows: int) -> None:
-    _check(lib().linear_set_split_rows(kv, rows), "linear_set_split_rows")
+def linear_set_tuning(kv: int, groups_per_wave: int = 0, n_split: int = 0) -> None:
+    _check(lib().linear_set_tuning(kv, groups_per_wave, n_split), "linear_set_tuning")
 
 
 def kv_free(kv: int) -> None:

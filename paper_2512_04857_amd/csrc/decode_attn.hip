@@ -1,269 +1,379 @@
-// Split-K single-query decode attention over the compact LineAR cache, with the append
-// of the new (k, v) (Eq. 2-4) and the per-query saliency term of Eq. 9 fused in.
+// Single-query decode attention over the compact LineAR cache, with the append of the new
+// (k, v) (Eq. 2-4) and the per-query saliency term of Eq. 9 fused in.
 //
-// Shape of the work: per (sequence, head) pair one query attends to T keys of d
-// elements; K and V rows are each read exactly once, there is no reuse between pairs,
-// so the step is a pure HBM stream (1 flop per byte at bf16) and runs on the vector
-// ALUs.  One workgroup (4 wavefronts) owns up to `rows_per_split` consecutive keys of
-// one pair.  A key row is spread over LPR = d*sizeof(elem)/16 adjacent lanes, 16 bytes
-// per lane, so every wave-wide load covers 1 KiB of contiguous cache.  All K and V
-// loads of a 128-key tile are issued before the first use; logits are reduced across
-// the LPR lanes of a row with lane shuffles; each wavefront keeps its own running
-// (max, sum, numerator) in fp32 and the four are merged once through LDS.  With more
-// than one split per pair the workgroup that finishes last (device-scope counter)
-// merges the split partials, so a step is a single launch.
+// Shape of the work: per (sequence, head) pair one query attends to T keys of d elements;
+// every K and V row is read exactly once and nothing is shared between pairs, so the step
+// is an HBM stream (1 flop per byte at bf16) that runs on the vector ALUs -- and at 8 TB/s
+// the ALU budget is only a few hundred instructions per wavefront, so the kernel is built
+// around instruction count as much as around bytes:
+//   * a key row is spread over LPR = d*sizeof(elem)/16 adjacent lanes (16 bytes each), so a
+//     wave-wide load covers 1 KiB of contiguous cache; a wavefront owns up to U such row
+//     groups and issues all its K loads, then all its V loads, before the first use;
+//   * q.k uses the packed bf16 dot instruction (fp32 accumulate) and a DPP butterfly over
+//     the LPR lanes; no LDS, no ds_bpermute in the main phase;
+//   * every group of LPR lanes is an independent softmax worker over its own rows (max and
+//     sum stay in-lane); workers meet once, in LDS, where the first wavefront merges them;
+//   * the new token is one extra row taken from the inputs by a single wavefront, which
+//     also writes it to the cache (Eq. 4);
+//   * a pair whose keys fit one workgroup (up to 144 row groups) is a single launch with
+//     no inter-workgroup traffic; longer ones are split over workgroups and merged by
+//     a second, tiny kernel (a kernel boundary is cheaper here than device-scope fences).
 #include "kernels.h"
 
 namespace linear {
 namespace {
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+constexpr int kXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kHalfMirror = 0x141; // lane i <- lane 7-i of its 8-lane half row
+constexpr int kMirror = 0x140;     // lane i <- lane 15-i of its 16-lane row
+
+// Sum over the aligned group of W adjacent lanes, result in every lane of the group.
+template <int W>
+__device__ __forceinline__ float sum_within(float x) {
+  x += dpp<kXor1>(x);
+  x += dpp<kXor2>(x);
+  if (W >= 8) x += dpp<kHalfMirror>(x);
+  if (W >= 16) x += dpp<kMirror>(x);
+  if (W >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+__device__ __forceinline__ float lane_bcast(float x, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  x = sum_within<16>(x);
+  return (lane_bcast(x, 0) + lane_bcast(x, 16)) + (lane_bcast(x, 32) + lane_bcast(x, 48));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp<kXor1>(x));
+  x = fmaxf(x, dpp<kXor2>(x));
+  x = fmaxf(x, dpp<kHalfMirror>(x));
+  x = fmaxf(x, dpp<kMirror>(x));
+  return fmaxf(fmaxf(lane_bcast(x, 0), lane_bcast(x, 16)), fmaxf(lane_bcast(x, 32), lane_bcast(x, 48)));
+}
 
 template <bool BF16>
 struct Elems;
 template <>
 struct Elems<true> {
   static constexpr int kPerLane = 8;
-  static __device__ __forceinline__ void unpack(const uint4& r, float (&f)[8]) {
-    f[0] = __uint_as_float(r.x << 16);
-    f[1] = __uint_as_float(r.x & 0xffff0000u);
-    f[2] = __uint_as_float(r.y << 16);
-    f[3] = __uint_as_float(r.y & 0xffff0000u);
-    f[4] = __uint_as_float(r.z << 16);
-    f[5] = __uint_as_float(r.z & 0xffff0000u);
-    f[6] = __uint_as_float(r.w << 16);
-    f[7] = __uint_as_float(r.w & 0xffff0000u);
+  static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
+    float r = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), 0.f, false);
+    r = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), r, false);
+    r = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), r, false);
+    r = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), r, false);
+    return r;
+  }
+  static __device__ __forceinline__ void axpy(float p, const uint4& r, float (&o)[8]) {
+    o[0] = __builtin_fmaf(p, __uint_as_float(r.x << 16), o[0]);
+    o[1] = __builtin_fmaf(p, __uint_as_float(r.x & 0xffff0000u), o[1]);
+    o[2] = __builtin_fmaf(p, __uint_as_float(r.y << 16), o[2]);
+    o[3] = __builtin_fmaf(p, __uint_as_float(r.y & 0xffff0000u), o[3]);
+    o[4] = __builtin_fmaf(p, __uint_as_float(r.z << 16), o[4]);
+    o[5] = __builtin_fmaf(p, __uint_as_float(r.z & 0xffff0000u), o[5]);
+    o[6] = __builtin_fmaf(p, __uint_as_float(r.w << 16), o[6]);
+    o[7] = __builtin_fmaf(p, __uint_as_float(r.w & 0xffff0000u), o[7]);
   }
 };
 template <>
 struct Elems<false> {
   static constexpr int kPerLane = 4;
-  static __device__ __forceinline__ void unpack(const uint4& r, float (&f)[4]) {
-    f[0] = __uint_as_float(r.x);
-    f[1] = __uint_as_float(r.y);
-    f[2] = __uint_as_float(r.z);
-    f[3] = __uint_as_float(r.w);
+  static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
+    float r = __uint_as_float(a.x) * __uint_as_float(b.x);
+    r = __builtin_fmaf(__uint_as_float(a.y), __uint_as_float(b.y), r);
+    r = __builtin_fmaf(__uint_as_float(a.z), __uint_as_float(b.z), r);
+    r = __builtin_fmaf(__uint_as_float(a.w), __uint_as_float(b.w), r);
+    return r;
+  }
+  static __device__ __forceinline__ void axpy(float p, const uint4& r, float (&o)[4]) {
+    o[0] = __builtin_fmaf(p, __uint_as_float(r.x), o[0]);
+    o[1] = __builtin_fmaf(p, __uint_as_float(r.y), o[1]);
+    o[2] = __builtin_fmaf(p, __uint_as_float(r.z), o[2]);
+    o[3] = __builtin_fmaf(p, __uint_as_float(r.w), o[3]);
   }
 };
 
-// Sum over the aligned group of W adjacent lanes.
-template <int W>
-__device__ __forceinline__ float sum_within(float x) {
-#pragma unroll
-  for (int o = W / 2; o > 0; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
-// Reductions over the lanes that share `lane % W` (one per row group of the wavefront).
-template <int W>
-__device__ __forceinline__ float sum_across(float x) {
-#pragma unroll
-  for (int o = 32; o >= W; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
-template <int W>
-__device__ __forceinline__ float max_across(float x) {
-#pragma unroll
-  for (int o = 32; o >= W; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
-}
+constexpr int kAccPrefetch = 4;   // accumulator entries per lane loaded ahead of their use
 
-// Adds this query's softmax probabilities on the mid keys to the line's accumulator
-// (Eq. 9, one row of the softmax).  `mid` holds the logits in log2 units.  Mode 0
-// normalises over the mid keys only; mode 1 uses the decode softmax's (m_all, l_all).
+// One row of the softmax in Eq. 9 added to the line's accumulator, by one wavefront.
+// `mid` holds the logits of the mid keys in log2 units.  Mode 0 normalises over the mid keys
+// only; mode 1 uses the decode softmax's (m_all, l_all).  `pre` holds acc[lane + 64 i].
 __device__ __forceinline__ void add_saliency(const float* mid, int mid_n, int mode, float m_all,
-                                             float l_all, float* acc) {
-  const int tid = threadIdx.x, lane = tid & 63;
+                                             float l_all, float* acc, const float (&pre)[kAccPrefetch]) {
+  const int lane = threadIdx.x & 63;
   float mx = m_all, z = l_all;
   if (mode == 0) {
     float lm = ninf();
     for (int j = lane; j < mid_n; j += 64) lm = fmaxf(lm, mid[j]);
-    lm = max_across<1>(lm);
+    lm = wave_max(lm);
     float ls = 0.f;
     for (int j = lane; j < mid_n; j += 64) ls += ex2(mid[j] - lm);
-    ls = sum_across<1>(ls);
     mx = lm;
-    z = ls;
+    z = wave_sum(ls);
   }
   const float inv = 1.0f / z;
-  for (int j = tid; j < mid_n; j += kBlock) acc[j] += ex2(mid[j] - mx) * inv;
+#pragma unroll
+  for (int i = 0; i < kAccPrefetch; ++i) {
+    const int j = lane + 64 * i;
+    if (j < mid_n) acc[j] = pre[i] + ex2(mid[j] - mx) * inv;
+  }
+  for (int j = lane + 64 * kAccPrefetch; j < mid_n; j += 64) acc[j] += ex2(mid[j] - mx) * inv;
 }
 
-template <bool BF16, int D>
-__global__ __launch_bounds__(kBlock) void decode_attn_kernel(const DecodeArgs a) {
-  using E = Elems<BF16>;
-  constexpr int EPL = E::kPerLane;        // elements per lane
-  constexpr int LPR = D / EPL;            // lanes per key row
-  constexpr int RPW = 64 / LPR;           // rows per wave-wide load
-  constexpr int U = kRowsPerIter / (4 * RPW);  // loads per lane per tile, per matrix
-
-  __shared__ float sm_o[4][D];
-  __shared__ float sm_m[4];
-  __shared__ float sm_l[4];
-  __shared__ int sm_last;
-  extern __shared__ float sm_mid[];       // mid logits when the pair is not split
-
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int seg = lane % LPR, sub = lane / LPR;
-  const int pair = blockIdx.x % a.n_pairs, split = blockIdx.x / a.n_pairs;
-  const int r0 = split * a.rows_per_split;
-  const int r1 = min(a.t, r0 + a.rows_per_split);
-  const int last_row = a.t - 1;
-
-  const uint4* kc = reinterpret_cast<const uint4*>(a.kc) + (size_t)pair * a.t_max * LPR + seg;
-  const uint4* vc = reinterpret_cast<const uint4*>(a.vc) + (size_t)pair * a.t_max * LPR + seg;
-  const uint4* kn = reinterpret_cast<const uint4*>(a.k_new) + (size_t)pair * LPR + seg;
-  const uint4* vn = reinterpret_cast<const uint4*>(a.v_new) + (size_t)pair * LPR + seg;
-
-  float qf[EPL];
-  {
-    const uint4 qr = reinterpret_cast<const uint4*>(a.q)[(size_t)pair * LPR + seg];
-    E::unpack(qr, qf);
+__device__ __forceinline__ void prefetch_acc(const float* acc, int mid_n, float (&pre)[kAccPrefetch]) {
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qf[e] *= a.scale_log2e;
+  for (int i = 0; i < kAccPrefetch; ++i) pre[i] = acc[min(lane + 64 * i, mid_n - 1)];
+}
+
+// Merge of n softmax partials (m[i], l[i], o[i][D]) by one wavefront, each partial being
+// the plain sum of G consecutive rows of pl / po (already scaled to the common m[i]).
+// Lane e (and e + 64) ends with the merged numerator; (m, l) are returned in every lane.
+template <int D, int G>
+__device__ __forceinline__ void merge_partials(const float* pm, const float* pl, const float* po,
+                                               int n, float& m_all, float& l_all, float (&o)[D / 64]) {
+  const int lane = threadIdx.x & 63;
+  m_all = ninf();
+  for (int i = 0; i < n; ++i) m_all = fmaxf(m_all, pm[i]);
+  l_all = 0.f;
+#pragma unroll
+  for (int c = 0; c < D / 64; ++c) o[c] = 0.f;
+  for (int i = 0; i < n; ++i) {
+    const float mi = pm[i];
+    const float f = mi > ninf() ? ex2(mi - m_all) : 0.f;   // a partial without keys
+    float ls = 0.f, os[D / 64];
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) os[c] = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      ls += pl[i * G + g];
+#pragma unroll
+      for (int c = 0; c < D / 64; ++c) os[c] += po[(size_t)(i * G + g) * D + c * 64 + lane];
+    }
+    l_all = __builtin_fmaf(ls, f, l_all);
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) o[c] = __builtin_fmaf(os[c], f, o[c]);
   }
+}
 
+template <int U>
+struct MaxWaves {   // waves per workgroup the register budget of a U-deep wavefront allows
+  static constexpr int value = U <= 8 ? 16 : (U <= 12 ? 12 : 8);
+};
+
+template <bool BF16, int D, int U>
+__global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(const DecodeArgs a) {
+  using E = Elems<BF16>;
+  constexpr int EPL = E::kPerLane;   // elements per lane
+  constexpr int LPR = D / EPL;       // lanes per key row
+  constexpr int RPW = 64 / LPR;      // rows per wave-wide load = softmax workers per wavefront
+
+  extern __shared__ float smem[];
+  const int nw = blockDim.x >> 6;
+  const int n_workers = nw * RPW;
+  float* sm_o = smem;                        // [n_workers][D] numerators, scaled to the wave's max
+  float* sm_l = sm_o + n_workers * D;        // [n_workers]    sums, likewise
+  float* sm_m = sm_l + n_workers;            // [nw]           the waves' maxima
+  float* sm_mid = sm_m + nw;                 // [mid_n]        logits of the mid keys
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int seg = lane % LPR, sub = lane / LPR;
+  const int pair = blockIdx.x, split = blockIdx.y;
+  const int r0 = split * a.rows_per_split;               // cached rows [r0, r0 + n_rows)
+  const int n_rows = min(a.t - 1, r0 + a.rows_per_split) - r0;
+  const int n_groups = (n_rows + RPW - 1) / RPW;
   const bool scoring = a.mid_n > 0;
-  float* mid_dst = a.n_split == 1 ? sm_mid : a.mid_logit + (size_t)pair * a.mid_n;
+  const bool finisher = wave == 0 && a.n_split == 1;
+  // The appended token is counted by sub-group 0 of the wavefront with the fewest row groups
+  // of the last split.
+  const bool owner_wave = split == a.n_split - 1 && wave == n_groups % nw;
+  const bool owner = owner_wave && sub == 0;
 
-  float m_run = ninf(), l_run = 0.f;
+  float acc_pre[kAccPrefetch];
+  if (finisher && scoring) prefetch_acc(a.acc + (size_t)pair * a.mid_n, a.mid_n, acc_pre);
+
+  // ---- loads: straight-line, so that every later wait counts exactly the loads behind it.
+  // Row groups beyond the end re-read the last row (served by the caches) and are masked.
+  const uint4* kc = reinterpret_cast<const uint4*>(a.kc) + ((size_t)pair * a.t_max + r0) * LPR + seg;
+  const uint4* vc = reinterpret_cast<const uint4*>(a.vc) + ((size_t)pair * a.t_max + r0) * LPR + seg;
+  const uint4 qr = reinterpret_cast<const uint4*>(a.q)[(size_t)pair * LPR + seg];
+  const uint4 knr = reinterpret_cast<const uint4*>(a.k_new)[(size_t)pair * LPR + seg];
+  const uint4 vnr = reinterpret_cast<const uint4*>(a.v_new)[(size_t)pair * LPR + seg];
+  uint4 kr[U], vr[U];
+  int row[U];
+  const int last = max(n_rows - 1, 0);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    row[u] = (u * nw + wave) * RPW + sub;
+    kr[u] = kc[(unsigned)min(row[u], last) * LPR];
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) vr[u] = vc[(unsigned)min(row[u], last) * LPR];
+
+  // ---- logits in log2 units and this worker's maximum (Eq. 2, numerically shifted)
+  float s[U];
+  float s_new = sum_within<LPR>(E::dot(knr, qr)) * a.scale_log2e;
+  s_new = owner ? s_new : ninf();
+  float m = s_new;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const float d = sum_within<LPR>(E::dot(kr[u], qr)) * a.scale_log2e;
+    s[u] = row[u] < n_rows ? d : ninf();
+    m = fmaxf(m, s[u]);
+  }
+  if (scoring) {
+    // Eq. 9: keep the logits of the mid keys for the line's saliency row.
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned j = (unsigned)(r0 + row[u] - a.mid_lo);
+      if (j < (unsigned)a.mid_n && seg == 0 && row[u] < n_rows) sm_mid[j] = s[u];
+    }
+  }
+  // ---- probabilities relative to the worker's own maximum, and its numerator
+  const float m_ref = m > ninf() ? m : 0.f;
   float o[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) o[e] = 0.f;
-
-  for (int base = r0; base < r1; base += kRowsPerIter) {
-    uint4 kr[U], vr[U];
-    // Row groups of RPW keys are dealt round-robin to the four wavefronts, so a short
-    // tile still keeps all of them busy.
-    const int row0 = base + wave * RPW + sub;
-    constexpr int kStep = 4 * RPW;
+  float l = ex2(s_new - m_ref);            // exp2(-inf) = 0 where the row does not count
+  E::axpy(l, vnr, o);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = row0 + u * kStep;
-      if (row < r1) {
-        const bool is_new = row == last_row;
-        kr[u] = *(is_new ? kn : kc + (size_t)row * LPR);
-        vr[u] = *(is_new ? vn : vc + (size_t)row * LPR);
-      } else {
-        kr[u] = make_uint4(0, 0, 0, 0);
-        vr[u] = make_uint4(0, 0, 0, 0);
-      }
-    }
-    // Eq. 4: the new pair becomes the last row of the cache.
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = row0 + u * kStep;
-      if (row == last_row && row < r1) {
-        reinterpret_cast<uint4*>(a.kc)[((size_t)pair * a.t_max + row) * LPR + seg] = kr[u];
-        reinterpret_cast<uint4*>(a.vc)[((size_t)pair * a.t_max + row) * LPR + seg] = vr[u];
-        if (seg == 0) a.pos[(size_t)pair * a.t_max + row] = a.new_pos;
-      }
-    }
-    float s[U];
-    float m_it = ninf();
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = row0 + u * kStep;
-      float kf[EPL];
-      E::unpack(kr[u], kf);
-      float dot = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) dot = __builtin_fmaf(qf[e], kf[e], dot);
-      dot = sum_within<LPR>(dot);
-      s[u] = row < r1 ? dot : ninf();
-      m_it = fmaxf(m_it, s[u]);
-      if (scoring && seg == 0 && row < r1) {
-        const int j = row - a.mid_lo;
-        if (j >= 0 && j < a.mid_n) mid_dst[j] = s[u];
-      }
-    }
-    m_it = max_across<LPR>(m_it);
-    const float m_new = fmaxf(m_run, m_it);
-    if (m_new > ninf()) {                 // wave-uniform: this wavefront has seen a key
-      const float corr = ex2(m_run - m_new);
-      l_run *= corr;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) o[e] *= corr;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float p = ex2(s[u] - m_new);  // exp2(-inf) = 0 for rows past the end
-        l_run += p;
-        float vf[EPL];
-        E::unpack(vr[u], vf);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) o[e] = __builtin_fmaf(p, vf[e], o[e]);
-      }
-      m_run = m_new;
-    }
+  for (int u = 0; u < U; ++u) {
+    const float p = ex2(s[u] - m_ref);
+    l += p;
+    E::axpy(p, vr[u], o);
   }
-
-  // Merge the row groups of the wavefront, then the four wavefronts.
-  l_run = sum_across<LPR>(l_run);
+  // ---- the wavefront's workers move to a common maximum and meet in LDS
+  const float m_wave = wave_max(m);
+  {
+    const float f = m > ninf() ? ex2(m - m_wave) : 0.f;
+    l *= f;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) o[e] = sum_across<LPR>(o[e]);
-  if (sub == 0) {
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) sm_o[wave][seg * EPL + e] = o[e];
+    for (int e = 0; e < EPL; ++e) o[e] *= f;
+    const int worker = wave * RPW + sub;
+    float4* dst = reinterpret_cast<float4*>(sm_o + worker * D + seg * EPL);
+    dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+    if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+    if (seg == 0) sm_l[worker] = l;
+    if (lane == 0) sm_m[wave] = m_wave;
   }
-  if (lane == 0) {
-    sm_m[wave] = m_run;
-    sm_l[wave] = l_run;
+  if (owner) {
+    // Eq. 4: the new pair becomes row T-1 of the cache.
+    const size_t dst = ((size_t)pair * a.t_max + (a.t - 1)) * LPR + seg;
+    reinterpret_cast<uint4*>(a.kc)[dst] = knr;
+    reinterpret_cast<uint4*>(a.vc)[dst] = vnr;
+    if (seg == 0) a.pos[(size_t)pair * a.t_max + (a.t - 1)] = a.new_pos;
   }
   __syncthreads();
-  float m_blk = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
-  float l_blk = 0.f, o_blk = 0.f;
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    const float f = sm_m[w] > ninf() ? ex2(sm_m[w] - m_blk) : 0.f;   // wavefront without keys
-    l_blk += sm_l[w] * f;
-    if (tid < D) o_blk += sm_o[w][tid] * f;
-  }
+  if (wave != 0) return;
 
+  float m_all, l_all, o_all[D / 64];
+  merge_partials<D, RPW>(sm_m, sm_l, sm_o, nw, m_all, l_all, o_all);
   if (a.n_split == 1) {
-    if (tid < D) a.out[(size_t)pair * D + tid] = o_blk / l_blk;
-    if (scoring) add_saliency(sm_mid, a.mid_n, a.score_mode, m_blk, l_blk, a.acc + (size_t)pair * a.mid_n);
+    const float inv = 1.0f / l_all;
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) a.out[(size_t)pair * D + c * 64 + lane] = o_all[c] * inv;
+    if (scoring)
+      add_saliency(sm_mid, a.mid_n, a.score_mode, m_all, l_all, a.acc + (size_t)pair * a.mid_n, acc_pre);
     return;
   }
+  const size_t pidx = (size_t)pair * a.max_split + split;
+#pragma unroll
+  for (int c = 0; c < D / 64; ++c) a.part_o[pidx * D + c * 64 + lane] = o_all[c];
+  if (lane == 0) {
+    a.part_ml[pidx * 2 + 0] = m_all;
+    a.part_ml[pidx * 2 + 1] = l_all;
+  }
+  if (scoring) {
+    // this workgroup's share of the mid logits goes to the merge kernel
+    const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
+    for (int j = j0 + lane; j < j1; j += 64) a.mid_logit[(size_t)pair * a.mid_n + j] = sm_mid[j];
+  }
+}
 
+// Second kernel of a split step: merges the split partials of one pair and finishes the
+// saliency row.  One wavefront per pair.
+template <int D>
+__global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) {
+  __shared__ float sm_m[kMaxSplit], sm_l[kMaxSplit];
+  const int lane = threadIdx.x, pair = blockIdx.x;
+  const bool scoring = a.mid_n > 0;
+  float acc_pre[kAccPrefetch];
+  if (scoring) prefetch_acc(a.acc + (size_t)pair * a.mid_n, a.mid_n, acc_pre);
   const size_t pbase = (size_t)pair * a.max_split;
-  if (tid < D) a.part_o[(pbase + split) * D + tid] = o_blk;
-  if (tid == 0) {
-    a.part_ml[(pbase + split) * 2 + 0] = m_blk;
-    a.part_ml[(pbase + split) * 2 + 1] = l_blk;
+  for (int i = lane; i < a.n_split; i += 64) {
+    sm_m[i] = a.part_ml[(pbase + i) * 2 + 0];
+    sm_l[i] = a.part_ml[(pbase + i) * 2 + 1];
   }
-  __threadfence();                          // publish partials and mid logits device-wide
   __syncthreads();
-  if (tid == 0) sm_last = atomicAdd(&a.counter[pair], 1) == a.n_split - 1;
-  __syncthreads();
-  if (!sm_last) return;
-  __threadfence();                          // observe the other workgroups' partials
-
-  float m_all = ninf();
-  for (int sidx = 0; sidx < a.n_split; ++sidx)
-    m_all = fmaxf(m_all, a.part_ml[(pbase + sidx) * 2]);
-  float l_all = 0.f, o_all = 0.f;
-  for (int sidx = 0; sidx < a.n_split; ++sidx) {
-    const float ms = a.part_ml[(pbase + sidx) * 2];
-    const float f = ms > ninf() ? ex2(ms - m_all) : 0.f;
-    l_all += a.part_ml[(pbase + sidx) * 2 + 1] * f;
-    if (tid < D) o_all += a.part_o[(pbase + sidx) * D + tid] * f;
-  }
-  if (tid < D) a.out[(size_t)pair * D + tid] = o_all / l_all;
-  if (tid == 0) a.counter[pair] = 0;        // ready for the next launch
+  float m_all, l_all, o_all[D / 64];
+  merge_partials<D, 1>(sm_m, sm_l, a.part_o + pbase * D, a.n_split, m_all, l_all, o_all);
+  const float inv = 1.0f / l_all;
+#pragma unroll
+  for (int c = 0; c < D / 64; ++c) a.out[(size_t)pair * D + c * 64 + lane] = o_all[c] * inv;
   if (scoring)
     add_saliency(a.mid_logit + (size_t)pair * a.mid_n, a.mid_n, a.score_mode, m_all, l_all,
-                 a.acc + (size_t)pair * a.mid_n);
+                 a.acc + (size_t)pair * a.mid_n, acc_pre);
+}
+
+template <bool BF16, int D, int U>
+hipError_t launch_main(const DecodeArgs& a, hipStream_t s) {
+  constexpr int RPW = 64 / (D / Elems<BF16>::kPerLane);
+  const int workers = a.n_waves * RPW;
+  const size_t dyn = ((size_t)workers * (D + 1) + a.n_waves + (size_t)a.mid_n) * sizeof(float);
+  const dim3 grid((unsigned)a.n_pairs, (unsigned)a.n_split), block(64u * (unsigned)a.n_waves);
+  hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U>), grid, block, dyn, s, a);
+  return hipGetLastError();
 }
 
 template <bool BF16, int D>
 hipError_t launch_t(const DecodeArgs& a, hipStream_t s) {
-  const size_t dyn = a.n_split == 1 ? (size_t)a.mid_n * sizeof(float) : 0;
-  const dim3 grid((unsigned)a.n_pairs * (unsigned)a.n_split);
-  hipLaunchKernelGGL((decode_attn_kernel<BF16, D>), grid, dim3(kBlock), dyn, s, a);
+  hipError_t e;
+  switch (a.depth) {
+    case 1: e = launch_main<BF16, D, 1>(a, s); break;
+    case 2: e = launch_main<BF16, D, 2>(a, s); break;
+    case 3: e = launch_main<BF16, D, 3>(a, s); break;
+    case 4: e = launch_main<BF16, D, 4>(a, s); break;
+    case 5: e = launch_main<BF16, D, 5>(a, s); break;
+    case 6: e = launch_main<BF16, D, 6>(a, s); break;
+    case 7: e = launch_main<BF16, D, 7>(a, s); break;
+    case 8: e = launch_main<BF16, D, 8>(a, s); break;
+    case 10: e = launch_main<BF16, D, 10>(a, s); break;
+    case 12: e = launch_main<BF16, D, 12>(a, s); break;
+    case 14: e = launch_main<BF16, D, 14>(a, s); break;
+    case 16: e = launch_main<BF16, D, 16>(a, s); break;
+    default: return hipErrorInvalidValue;
+  }
+  if (e != hipSuccess || a.n_split == 1) return e;
+  hipLaunchKernelGGL((decode_combine_kernel<D>), dim3((unsigned)a.n_pairs), dim3(64), 0, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
+
+int decode_rows_per_group(int dtype, int head_dim) {
+  const int lanes_per_row = head_dim / (dtype == 1 ? 8 : 4);
+  return 64 / lanes_per_row;
+}
+
+int decode_max_waves(int depth) { return depth <= 8 ? 16 : (depth <= 12 ? 12 : 8); }
+
+int decode_depth_for(int groups_per_wave) {
+  static const int kDepths[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
+  for (int d : kDepths)
+    if (d >= groups_per_wave) return d;
+  return 0;
+}
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, int head_dim, hipStream_t s) {
   if (dtype == 1 && head_dim == 64) return launch_t<true, 64>(a, s);

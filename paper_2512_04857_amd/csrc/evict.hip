@@ -112,6 +112,15 @@ __global__ __launch_bounds__(kBlock) void copy_rows_kernel(uint4* dst, int64_t d
   }
 }
 
+__global__ __launch_bounds__(kBlock) void zero_rows_kernel(uint4* dst, int64_t dst_pitch,
+                                                           int64_t pieces_per_pair, int64_t total) {
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * kBlock) {
+    const int64_t p = i / pieces_per_pair, r = i % pieces_per_pair;
+    dst[p * dst_pitch + r] = make_uint4(0, 0, 0, 0);
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void iota_rows_kernel(int32_t* pos, int64_t pitch, int32_t rows,
                                                            int64_t total) {
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
@@ -173,6 +182,16 @@ hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,
   hipLaunchKernelGGL(copy_rows_kernel, dim3(grid_for((size_t)total)), dim3(kBlock), 0, s,
                      reinterpret_cast<uint4*>(dst), dst_pitch_rows * ppr,
                      reinterpret_cast<const uint4*>(src), src_pitch_rows * ppr, per_pair, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_rows(void* dst, int64_t dst_pitch_rows, int32_t rows, int32_t n_pairs,
+                            int32_t row_bytes, hipStream_t s) {
+  if (rows <= 0 || n_pairs <= 0) return hipSuccess;
+  const int64_t ppr = row_bytes / 16;
+  const int64_t per_pair = (int64_t)rows * ppr, total = per_pair * n_pairs;
+  hipLaunchKernelGGL(zero_rows_kernel, dim3(grid_for((size_t)total)), dim3(kBlock), 0, s,
+                     reinterpret_cast<uint4*>(dst), dst_pitch_rows * ppr, per_pair, total);
   return hipGetLastError();
 }
 

@@ -6,8 +6,8 @@
 
 namespace linear {
 
-constexpr int kBlock = 256;        // 4 wavefronts of 64
-constexpr int kRowsPerIter = 128;  // keys one workgroup holds in registers at a time
+constexpr int kBlock = 256;        // workgroup size of the eviction and copy kernels
+constexpr int kMaxSplit = 64;      // workgroups one pair's keys may be split over
 
 // One decode step of one layer (Eq. 2-4 plus the per-query term of Eq. 9).
 struct DecodeArgs {
@@ -21,14 +21,15 @@ struct DecodeArgs {
   float* part_o;      // [P, max_split, d]   split partial numerators
   float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
   float* mid_logit;   // [P, mid_n]          logits of the mid keys when n_split > 1
-  int32_t* counter;   // [P]                 zero between launches
   float* acc;         // [P, mid_n]          running sum over the line's queries
   int32_t n_pairs;    // P = Bz * H
   int32_t t;          // keys visible to this query, the new one included
   int32_t t_max;      // row pitch of the caches, in keys
-  int32_t rows_per_split;
-  int32_t n_split;
-  int32_t max_split;
+  int32_t rows_per_split;  // cached keys per workgroup (a multiple of the row-group size)
+  int32_t n_split;    // workgroups per pair
+  int32_t n_waves;    // wavefronts per workgroup
+  int32_t depth;      // row groups a wavefront holds (an instantiated value, see decode_depth_for)
+  int32_t max_split;  // pitch of the partial buffers
   int32_t mid_lo;     // first mid key (cache row index)
   int32_t mid_n;      // mid keys to score at this step (0: none)
   int32_t score_mode;
@@ -51,11 +52,17 @@ struct EvictArgs {
 };
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, int head_dim, hipStream_t s);
+int decode_rows_per_group(int dtype, int head_dim);   // keys one wave-wide load covers
+int decode_max_waves(int depth);                      // wavefronts per workgroup at that depth
+int decode_depth_for(int groups_per_wave);            // smallest instantiated depth >= the argument, 0 if none
 hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s);
 
 // dst[p, 0:rows, :] = src[p, 0:rows, :] for p < n_pairs; pitches in rows; row_bytes % 16 == 0.
 hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,
                             int64_t src_pitch_rows, int32_t rows, int32_t n_pairs,
+                            int32_t row_bytes, hipStream_t s);
+// dst[p, 0:rows, :] = 0.
+hipError_t launch_zero_rows(void* dst, int64_t dst_pitch_rows, int32_t rows, int32_t n_pairs,
                             int32_t row_bytes, hipStream_t s);
 // pos[p, j] = j for j < rows.
 hipError_t launch_iota_rows(int32_t* pos, int64_t pitch, int32_t rows, int32_t n_pairs,

@@ -4,6 +4,7 @@
 // read the device back) and the kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <new>
@@ -31,10 +32,10 @@ struct Derived {
   int mid_n;        // B - N_init - r n   (0 when nothing is ever evicted)
   int n_tail;       // r n
   int first_line;   // B / n: first line (1-based) that ends in an eviction
-  int max_split;    // ceil(t_max / 128)
+  int max_split;    // pitch of the split-partial buffers
   float scale;
   // scratch layout (byte offsets)
-  size_t off_acc, off_pos, off_part_o, off_part_ml, off_mid, off_counter, total;
+  size_t off_acc, off_pos, off_part_o, off_part_ml, off_mid, total;
   size_t acc_layer, pos_layer;   // element strides per layer
 };
 
@@ -63,7 +64,7 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->mid_n = d->compresses ? c.budget - c.n_init - d->n_tail : 0;
   if (d->mid_n > kMaxMid) return LINEAR_EINVAL;
   d->first_line = c.budget / c.line_len;
-  d->max_split = (d->t_max + linear::kRowsPerIter - 1) / linear::kRowsPerIter;
+  d->max_split = linear::kMaxSplit;
   d->scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.head_dim);
   const size_t P = (size_t)d->pairs;
   d->acc_layer = P * (size_t)d->mid_n;
@@ -74,7 +75,6 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->off_part_o = off;   off = align_up(off + P * d->max_split * c.head_dim * sizeof(float));
   d->off_part_ml = off;  off = align_up(off + P * d->max_split * 2 * sizeof(float));
   d->off_mid = off;      off = align_up(off + P * (size_t)d->mid_n * sizeof(float));
-  d->off_counter = off;  off = align_up(off + P * sizeof(int32_t));
   d->total = off;
   return LINEAR_OK;
 }
@@ -100,16 +100,61 @@ struct linear_kv {
   std::vector<void*> k_cache, v_cache;
   char* scratch;
   std::vector<LayerState> layer;
-  int split_rows;
+  int groups_per_wave;   // tuning: row groups a wavefront should take (1..16)
+  int force_split;       // tuning: 0 = automatic
 };
 
 namespace {
 
-int default_split_rows(const linear_kv& kv) {
-  // Short caches: one workgroup per pair while there are at least two pairs per compute
-  // unit; otherwise 128-key splits so that the launch still fills the 256 CUs.
-  (void)kv;
-  return linear::kRowsPerIter;
+constexpr int kDefaultGroupsPerWave = 8;
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Launch shape of one decode step: how the cached keys of a pair are dealt to workgroups
+// (splits) and wavefronts.  A wavefront holds up to `depth` row groups in registers; a
+// workgroup of up to decode_max_waves(depth) wavefronts holds a whole pair when it can
+// (one launch); longer caches, or too few pairs to fill 256 CUs, are split.
+struct Plan {
+  int n_split, rows_per_split, n_waves, depth;
+};
+
+bool make_plan(const linear_kv& kv, int cached_rows, Plan* p) {
+  const int rpg = linear::decode_rows_per_group(kv.cfg.dtype, kv.cfg.head_dim);
+  const int groups = ceil_div(cached_rows, rpg);
+  const int target = kv.groups_per_wave;
+  int n_split = kv.force_split;
+  if (n_split == 0) {
+    n_split = 1;
+    if (groups > 144) n_split = ceil_div(groups, 128);
+    if (kv.d.pairs < 256 && groups >= 32) {   // few pairs: split to put ~256 workgroups in flight
+      const int want = std::min(ceil_div(256, kv.d.pairs), groups / 16);
+      n_split = std::max(n_split, want);
+    }
+  }
+  if (n_split > linear::kMaxSplit) return false;
+  int gps = ceil_div(groups, n_split);                    // row groups per split
+  while (n_split > 1 && (int64_t)(n_split - 1) * gps * rpg >= cached_rows) {   // no empty split
+    --n_split;
+    gps = ceil_div(groups, n_split);
+  }
+  if (gps < 1) gps = 1;
+  // Wavefronts per workgroup: enough for `target` row groups each, at least as many as the
+  // deepest kernel needs, at most what the register budget of the resulting depth allows.
+  int nw = std::min(16, std::max(ceil_div(gps, target), ceil_div(gps, 16)));
+  for (int tries = 0; tries < 4; ++tries) {
+    const int depth = linear::decode_depth_for(ceil_div(gps, nw));
+    if (depth == 0) return false;
+    const int maxw = linear::decode_max_waves(depth);
+    if (nw <= maxw) {
+      p->n_split = n_split;
+      p->rows_per_split = gps * rpg;
+      p->depth = depth;
+      p->n_waves = nw;
+      return true;
+    }
+    nw = maxw;   // too many wavefronts for this depth: fewer, deeper ones
+  }
+  return false;
 }
 
 bool line_evicts(const linear_kv& kv, int line /*1-based*/) {
@@ -157,7 +202,8 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
     kv->v_cache.assign(v_cache, v_cache + cfg->n_layers);
     kv->scratch = static_cast<char*>(scratch);
     kv->layer.assign(cfg->n_layers, LayerState());
-    kv->split_rows = default_split_rows(*kv);
+    kv->groups_per_wave = kDefaultGroupsPerWave;
+    kv->force_split = 0;
   } catch (...) {   // host allocation failure must not cross the C boundary
     delete kv;
     return LINEAR_EINVAL;
@@ -165,12 +211,16 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
-  // Accumulators and split counters start at zero; position maps start with the prefix.
+  // Accumulators start at zero; position maps start with the prefix.
   e = linear::launch_fill_u32(kv->scratch + d.off_acc, 0u, d.acc_layer * cfg->n_layers, s);
-  if (e == hipSuccess) e = linear::launch_fill_u32(kv->scratch + d.off_counter, 0u, (size_t)d.pairs, s);
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
     int32_t* pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * l;
     e = linear::launch_iota_rows(pos, d.t_max, cfg->n_cond, d.pairs, s);
+    if (e == hipSuccess && cfg->n_cond == 0) {
+      // With an empty cache the first step's masked loads touch row 0: give it defined bits.
+      e = linear::launch_zero_rows(kv->k_cache[l], d.t_max, 1, d.pairs, d.row_bytes, s);
+      if (e == hipSuccess) e = linear::launch_zero_rows(kv->v_cache[l], d.t_max, 1, d.pairs, d.row_bytes, s);
+    }
     if (e == hipSuccess && cfg->n_cond > 0)
       e = linear::launch_copy_rows(kv->k_cache[l], d.t_max, k_cond[l], cfg->n_cond, cfg->n_cond,
                                    d.pairs, d.row_bytes, s);
@@ -211,16 +261,17 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
   a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
   a.mid_logit = reinterpret_cast<float*>(kv->scratch + d.off_mid);
-  a.counter = reinterpret_cast<int32_t*>(kv->scratch + d.off_counter);
   a.acc = reinterpret_cast<float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
   a.n_pairs = d.pairs;
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
-  a.n_split = (a.t + kv->split_rows - 1) / kv->split_rows;
-  a.rows_per_split = (a.t + a.n_split - 1) / a.n_split;
+  Plan plan;
+  if (!make_plan(*kv, a.t - 1, &plan)) return LINEAR_EINVAL;
+  a.n_split = plan.n_split;
+  a.rows_per_split = plan.rows_per_split;
+  a.n_waves = plan.n_waves;
+  a.depth = plan.depth;
   a.max_split = d.max_split;
-  if (a.n_split > d.max_split || (int64_t)(a.n_split - 1) * a.rows_per_split >= a.t)
-    return LINEAR_EINVAL;
   a.mid_lo = d.mid_lo;
   a.mid_n = line_evicts(*kv, line) ? d.mid_n : 0;
   a.score_mode = c.score_mode;
@@ -259,6 +310,32 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
   }
   ls.in_line = 0;
   ls.lines_done += 1;
+  return LINEAR_OK;
+}
+
+int decode_step_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, const void* q,
+                       const void* k, const void* v, void* out, size_t qkv_stride,
+                       size_t out_stride, void* stream) {
+  if (!kv || !q || !k || !v || !out) return LINEAR_ENULL;
+  if (count < 0 || first_layer < 0 || (int64_t)first_layer + count > kv->cfg.n_layers) return LINEAR_EINVAL;
+  if ((qkv_stride | out_stride) & 15u) return LINEAR_EALIGN;
+  for (int32_t i = 0; i < count; ++i) {
+    const int rc = decode_step(kv, first_layer + i, static_cast<const char*>(q) + i * qkv_stride,
+                               static_cast<const char*>(k) + i * qkv_stride,
+                               static_cast<const char*>(v) + i * qkv_stride,
+                               static_cast<char*>(out) + i * out_stride, stream);
+    if (rc != LINEAR_OK) return rc;
+  }
+  return LINEAR_OK;
+}
+
+int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, void* stream) {
+  if (!kv) return LINEAR_ENULL;
+  if (count < 0 || first_layer < 0 || (int64_t)first_layer + count > kv->cfg.n_layers) return LINEAR_EINVAL;
+  for (int32_t i = 0; i < count; ++i) {
+    const int rc = end_of_line_evict(kv, first_layer + i, stream);
+    if (rc != LINEAR_OK) return rc;
+  }
   return LINEAR_OK;
 }
 
@@ -312,14 +389,12 @@ int kv_length(const linear_kv_t* kv, int32_t layer, int32_t* cached_tokens, int3
   return LINEAR_OK;
 }
 
-int linear_set_split_rows(linear_kv_t* kv, int32_t rows) {
+int linear_set_tuning(linear_kv_t* kv, int32_t groups_per_wave, int32_t n_split) {
   if (!kv) return LINEAR_ENULL;
-  if (rows == 0) {
-    kv->split_rows = default_split_rows(*kv);
-    return LINEAR_OK;
-  }
-  if (rows < linear::kRowsPerIter || rows % linear::kRowsPerIter) return LINEAR_EINVAL;
-  kv->split_rows = rows;
+  if (groups_per_wave < 0 || groups_per_wave > 16 || n_split < 0 || n_split > linear::kMaxSplit)
+    return LINEAR_EINVAL;
+  kv->groups_per_wave = groups_per_wave ? groups_per_wave : kDefaultGroupsPerWave;
+  kv->force_split = n_split;
   return LINEAR_OK;
 }
 

@@ -65,20 +65,18 @@ class ParityReport:
                 f"sanctioned={self.sanctioned} min_gap={self.min_gap:.3e}")
 
 
-def run_parity(w, slices, *, device="cuda:0", score_mode=0, split_rows=0, steps=None,
-               seed=synth.BASE_SEED, check_scores=True, progress=None) -> ParityReport:
+def run_parity(w, slices, *, device="cuda:0", score_mode=0, groups_per_wave=0, n_split=0, steps=None,
+               seed=synth.BASE_SEED, check_scores=True, progress=None, layers_call=False) -> ParityReport:
     """Runs workload `w` on the GPU at its full shape and the oracle on `slices`
     ((layer, sequence, head) triples).  Raises AssertionError on disagreement."""
     o = oracle()
     rep = ParityReport()
     cfg = binding.cfg_from_workload(w, score_mode=score_mode)
     cache = binding.LineARCache(cfg, device)
-    if split_rows:
-        pass  # applied after start_image (needs the handle)
     kc, vc = synth.cond_kv(w, device, seed)
     cache.start_image(kc, vc)
-    if split_rows:
-        binding.linear_set_split_rows(cache.handle, split_rows)
+    if groups_per_wave or n_split:
+        binding.linear_set_tuning(cache.handle, groups_per_wave, n_split)
 
     li = torch.tensor([s[0] for s in slices], device=device)
     bi = torch.tensor([s[1] for s in slices], device=device)
@@ -97,8 +95,13 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, split_rows=0, steps=
     mid_n = w.budget - w.n_init - w.n_recent_lines * n
     for step in range(N):
         q, k, v = synth.step_qkv(w, step, device, seed)
-        for l in range(w.n_layers):
-            cache.decode_step(l, q[l], k[l], v[l], out[l])
+        if layers_call:     # the multi-layer entry points, as the benchmark uses them
+            binding.decode_step_layers(cache.handle, 0, w.n_layers, q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                       out.data_ptr(), q[0].numel() * q.element_size(), out[0].numel() * 4,
+                                       cache.stream())
+        else:
+            for l in range(w.n_layers):
+                cache.decode_step(l, q[l], k[l], v[l], out[l])
         line_q.append(q[li, bi, hi])
         line_k.append(k[li, bi, hi])
         line_v.append(v[li, bi, hi])
@@ -122,8 +125,11 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, split_rows=0, steps=
         if evicting and check_scores:
             for l in layers_sampled:
                 gpu_scores[l] = cache.scores(l).cpu().numpy()
-        for l in range(w.n_layers):
-            cache.end_of_line_evict(l)
+        if layers_call:
+            binding.end_of_line_evict_layers(cache.handle, 0, w.n_layers, cache.stream())
+        else:
+            for l in range(w.n_layers):
+                cache.end_of_line_evict(l)
         gpu_pos = {}
         if evicting:
             for l in layers_sampled:

@@ -40,14 +40,19 @@ def test_tiny_full_budget_never_evicts():
     assert rep.evictions == 0 and rep.steps == 64
 
 
-@pytest.mark.parametrize("w,split_rows,score_mode", [
-    (MID_SPLIT, 0, 0), (MID_SPLIT, 0, 1), (LUMINA_SLICE, 0, 0), (LUMINA_SLICE, 256, 0),
-    (LUMINA_SLICE, 0, 1), (F32_R2, 0, 0), (FULL_SPLIT, 0, 0), (FULL_SPLIT, 256, 0), (NO_COND, 0, 0),
-    (F32_D64_LONG, 0, 0), (F32_D64_LONG, 0, 1), (STREAMING, 0, 0),
+# (workload, row groups per wavefront, forced splits, score mode): single-launch shapes with
+# 1..16 wavefronts and all three register depths, and split shapes (two launches) whose split
+# boundaries fall inside the mid region.
+@pytest.mark.parametrize("w,gpw,n_split,score_mode", [
+    (MID_SPLIT, 0, 0, 0), (MID_SPLIT, 1, 0, 1), (MID_SPLIT, 16, 0, 0), (MID_SPLIT, 3, 2, 0),
+    (MID_SPLIT, 0, 3, 1), (LUMINA_SLICE, 0, 0, 0), (LUMINA_SLICE, 12, 1, 0), (LUMINA_SLICE, 4, 5, 0),
+    (LUMINA_SLICE, 0, 2, 1), (F32_R2, 0, 0, 0), (F32_R2, 2, 2, 0), (FULL_SPLIT, 0, 0, 0),
+    (FULL_SPLIT, 16, 1, 0), (FULL_SPLIT, 5, 3, 0), (NO_COND, 0, 0, 0), (NO_COND, 1, 0, 0),
+    (F32_D64_LONG, 0, 0, 0), (F32_D64_LONG, 8, 2, 1), (STREAMING, 0, 0, 0),
 ], ids=lambda x: getattr(x, "name", str(x)))
-def test_mid_sizes_every_slice(w, split_rows, score_mode):
-    rep = run_parity(w, all_slices(w), split_rows=split_rows, score_mode=score_mode)
-    say(f"{w.name} split_rows {split_rows} mode {score_mode}: {rep}")
+def test_mid_sizes_every_slice(w, gpw, n_split, score_mode):
+    rep = run_parity(w, all_slices(w), groups_per_wave=gpw, n_split=n_split, score_mode=score_mode)
+    say(f"{w.name} groups/wave {gpw} splits {n_split} mode {score_mode}: {rep}")
     assert rep.steps == w.n_visual
 
 
@@ -62,7 +67,7 @@ def test_full_size_compressed_sampled_slices(w):
     """The benchmark's shapes and launch configuration; the oracle replays whole images
     for sampled (layer, sequence, head) slices, which is exact because slices never
     interact."""
-    rep = run_parity(w, _sample(w), progress=say if w.n_lines > 30 else None)
+    rep = run_parity(w, _sample(w), progress=say if w.n_lines > 30 else None, layers_call=True)
     say(f"{w.name}: {rep}")
     assert rep.steps == w.n_visual
     assert rep.evictions == (w.n_lines - w.budget // w.line_len) * len(_sample(w))
@@ -71,7 +76,7 @@ def test_full_size_compressed_sampled_slices(w):
 @pytest.mark.parametrize("w", [synth.LLAMAGEN_XL, synth.JANUS_PRO_7B], ids=lambda w: w.name)
 def test_full_size_full_cache_sampled_slices(w):
     wf = w.full_cache()
-    rep = run_parity(wf, _sample(wf, n_heads=2))
+    rep = run_parity(wf, _sample(wf, n_heads=2), layers_call=True)
     say(f"{wf.name}: {rep}")
     assert rep.steps == w.n_visual and rep.evictions == 0
 
@@ -122,7 +127,9 @@ def test_state_machine_errors():
         cache.decode_step(0, q[0], k[0], v[0], out)      # image complete
     assert e.value.code == binding.LINEAR_ESTATE
     with pytest.raises(binding.LinearError):
-        binding.linear_set_split_rows(cache.handle, 100)
+        binding.linear_set_tuning(cache.handle, 17, 0)
+    with pytest.raises(binding.LinearError):
+        binding.linear_set_tuning(cache.handle, 0, 65)
     torch.cuda.synchronize()
     cache.close()
 
