@@ -13,8 +13,11 @@
 //     the LPR lanes; no LDS, no ds_bpermute in the main phase;
 //   * every group of LPR lanes is an independent softmax worker over its own rows (max and
 //     sum stay in-lane); workers meet once, in LDS, where the first wavefront merges them;
-//   * the new token is one extra row taken from the inputs by a single wavefront, which
-//     also writes it to the cache (Eq. 4);
+//   * the new token is one extra row taken from the inputs; one wavefront counts it and
+//     writes it to the cache (Eq. 4);
+//   * on lines that end in an eviction the logits of the mid keys are appended to the line's
+//     guide queue (Eq. 8) through LDS; the softmax rows of Eq. 9 are evaluated once per line
+//     by the eviction kernel, so a decode step carries no reduction for them;
 //   * a pair whose keys fit one workgroup (up to 144 row groups) is a single launch with
 //     no inter-workgroup traffic; longer ones are split over workgroups and merged by
 //     a second, tiny kernel (a kernel boundary is cheaper here than device-scope fences).
@@ -49,10 +52,6 @@ __device__ __forceinline__ float sum_within(float x) {
 }
 __device__ __forceinline__ float lane_bcast(float x, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
-}
-__device__ __forceinline__ float wave_sum(float x) {
-  x = sum_within<16>(x);
-  return (lane_bcast(x, 0) + lane_bcast(x, 16)) + (lane_bcast(x, 32) + lane_bcast(x, 48));
 }
 __device__ __forceinline__ float wave_max(float x) {
   x = fmaxf(x, dpp<kXor1>(x));
@@ -102,39 +101,6 @@ struct Elems<false> {
     o[3] = __builtin_fmaf(p, __uint_as_float(r.w), o[3]);
   }
 };
-
-constexpr int kAccPrefetch = 4;   // accumulator entries per lane loaded ahead of their use
-
-// One row of the softmax in Eq. 9 added to the line's accumulator, by one wavefront.
-// `mid` holds the logits of the mid keys in log2 units.  Mode 0 normalises over the mid keys
-// only; mode 1 uses the decode softmax's (m_all, l_all).  `pre` holds acc[lane + 64 i].
-__device__ __forceinline__ void add_saliency(const float* mid, int mid_n, int mode, float m_all,
-                                             float l_all, float* acc, const float (&pre)[kAccPrefetch]) {
-  const int lane = threadIdx.x & 63;
-  float mx = m_all, z = l_all;
-  if (mode == 0) {
-    float lm = ninf();
-    for (int j = lane; j < mid_n; j += 64) lm = fmaxf(lm, mid[j]);
-    lm = wave_max(lm);
-    float ls = 0.f;
-    for (int j = lane; j < mid_n; j += 64) ls += ex2(mid[j] - lm);
-    mx = lm;
-    z = wave_sum(ls);
-  }
-  const float inv = 1.0f / z;
-#pragma unroll
-  for (int i = 0; i < kAccPrefetch; ++i) {
-    const int j = lane + 64 * i;
-    if (j < mid_n) acc[j] = pre[i] + ex2(mid[j] - mx) * inv;
-  }
-  for (int j = lane + 64 * kAccPrefetch; j < mid_n; j += 64) acc[j] += ex2(mid[j] - mx) * inv;
-}
-
-__device__ __forceinline__ void prefetch_acc(const float* acc, int mid_n, float (&pre)[kAccPrefetch]) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int i = 0; i < kAccPrefetch; ++i) pre[i] = acc[min(lane + 64 * i, mid_n - 1)];
-}
 
 // Merge of n softmax partials (m[i], l[i], o[i][D]) by one wavefront, each partial being
 // the plain sum of G consecutive rows of pl / po (already scaled to the common m[i]).
@@ -194,14 +160,10 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   const int n_rows = min(a.t - 1, r0 + a.rows_per_split) - r0;
   const int n_groups = (n_rows + RPW - 1) / RPW;
   const bool scoring = a.mid_n > 0;
-  const bool finisher = wave == 0 && a.n_split == 1;
   // The appended token is counted by sub-group 0 of the wavefront with the fewest row groups
   // of the last split.
   const bool owner_wave = split == a.n_split - 1 && wave == n_groups % nw;
   const bool owner = owner_wave && sub == 0;
-
-  float acc_pre[kAccPrefetch];
-  if (finisher && scoring) prefetch_acc(a.acc + (size_t)pair * a.mid_n, a.mid_n, acc_pre);
 
   // ---- loads: straight-line, so that every later wait counts exactly the loads behind it.
   // Row groups beyond the end re-read the last row (served by the caches) and are masked.
@@ -220,6 +182,9 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) vr[u] = vc[(unsigned)min(row[u], last) * LPR];
+  // Nothing below may be scheduled in front of the loads: a wait placed between them would
+  // hold back the rest of the requests for a full memory round trip.
+  __builtin_amdgcn_sched_barrier(0);
 
   // ---- logits in log2 units and this worker's maximum (Eq. 2, numerically shifted)
   float s[U];
@@ -233,7 +198,8 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     m = fmaxf(m, s[u]);
   }
   if (scoring) {
-    // Eq. 9: keep the logits of the mid keys for the line's saliency row.
+    // Eq. 8-9: the logits of the mid keys are staged in LDS (no vector-memory traffic while
+    // the V loads are in flight) and join the line's guide queue below.
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const unsigned j = (unsigned)(r0 + row[u] - a.mid_lo);
@@ -275,6 +241,13 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     if (seg == 0) a.pos[(size_t)pair * a.t_max + (a.t - 1)] = a.new_pos;
   }
   __syncthreads();
+  if (scoring && wave == nw - 1) {
+    // This workgroup's share of the query's guide-queue row, written by the last wavefront
+    // while the first one merges.
+    float* qrow = a.guide + (size_t)pair * a.guide_pitch;
+    const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
+    for (int j = j0 + lane; j < j1; j += 64) qrow[j] = sm_mid[j];
+  }
   if (wave != 0) return;
 
   float m_all, l_all, o_all[D / 64];
@@ -283,8 +256,11 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     const float inv = 1.0f / l_all;
 #pragma unroll
     for (int c = 0; c < D / 64; ++c) a.out[(size_t)pair * D + c * 64 + lane] = o_all[c] * inv;
-    if (scoring)
-      add_saliency(sm_mid, a.mid_n, a.score_mode, m_all, l_all, a.acc + (size_t)pair * a.mid_n, acc_pre);
+    if (scoring && lane == 0) {   // the decode softmax's statistics, for score mode 1
+      float* qrow = a.guide + (size_t)pair * a.guide_pitch;
+      qrow[a.mid_n] = m_all;
+      qrow[a.mid_n + 1] = l_all;
+    }
     return;
   }
   const size_t pidx = (size_t)pair * a.max_split + split;
@@ -294,22 +270,14 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     a.part_ml[pidx * 2 + 0] = m_all;
     a.part_ml[pidx * 2 + 1] = l_all;
   }
-  if (scoring) {
-    // this workgroup's share of the mid logits goes to the merge kernel
-    const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
-    for (int j = j0 + lane; j < j1; j += 64) a.mid_logit[(size_t)pair * a.mid_n + j] = sm_mid[j];
-  }
 }
 
-// Second kernel of a split step: merges the split partials of one pair and finishes the
-// saliency row.  One wavefront per pair.
+// Second kernel of a split step: merges the split partials of one pair.  One wavefront
+// per pair.
 template <int D>
 __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) {
   __shared__ float sm_m[kMaxSplit], sm_l[kMaxSplit];
   const int lane = threadIdx.x, pair = blockIdx.x;
-  const bool scoring = a.mid_n > 0;
-  float acc_pre[kAccPrefetch];
-  if (scoring) prefetch_acc(a.acc + (size_t)pair * a.mid_n, a.mid_n, acc_pre);
   const size_t pbase = (size_t)pair * a.max_split;
   for (int i = lane; i < a.n_split; i += 64) {
     sm_m[i] = a.part_ml[(pbase + i) * 2 + 0];
@@ -321,9 +289,11 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
   const float inv = 1.0f / l_all;
 #pragma unroll
   for (int c = 0; c < D / 64; ++c) a.out[(size_t)pair * D + c * 64 + lane] = o_all[c] * inv;
-  if (scoring)
-    add_saliency(a.mid_logit + (size_t)pair * a.mid_n, a.mid_n, a.score_mode, m_all, l_all,
-                 a.acc + (size_t)pair * a.mid_n, acc_pre);
+  if (a.mid_n > 0 && lane == 0) {
+    float* qrow = a.guide + (size_t)pair * a.guide_pitch;
+    qrow[a.mid_n] = m_all;
+    qrow[a.mid_n + 1] = l_all;
+  }
 }
 
 template <bool BF16, int D, int U>

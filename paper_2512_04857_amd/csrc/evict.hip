@@ -1,60 +1,131 @@
-// End-of-line eviction (Eq. 10) and in-place gather-compaction (Eq. 5-7), plus the small
+// End-of-line work: saliency of the mid candidates from the line's guide queue (Eq. 9),
+// BottomK selection (Eq. 10) and in-place gather-compaction (Eq. 5-7), plus the small
 // copy / fill kernels of kv_init and kv_gather.
 //
-// One workgroup per (sequence, head) pair.  The accumulated saliency of the mid candidates
-// is ranked by counting (stable: equal scores rank by age), the n lowest are dropped, the
-// survivors and the r recent lines slide down over the holes.  Rows only ever move to a
-// lower or equal index and keep their order, so processing destination rows in ascending
-// tiles -- load the tile's source rows into registers, barrier, store -- never overwrites
-// a row that is still to be read.
+// One workgroup per (sequence, head) pair.  The queue holds, for each of the line's n
+// queries, its logits on the mid keys; the workgroup copies it to LDS, takes every row's
+// softmax statistics, and adds the rows up column by column in a fixed order (so the result
+// does not depend on timing).  The candidates are ranked by counting (stable: equal
+// scores rank by age), the n lowest are dropped, the survivors and the r recent lines slide
+// down over the holes.  Rows only ever move to a lower or equal index and keep their order,
+// so processing destination rows in ascending tiles -- load the tile's source rows into
+// registers, barrier, store -- never overwrites a row that is still to be read.
 #include "kernels.h"
 
 namespace linear {
 namespace {
 
 constexpr int kPiecesPerThread = 4;   // 16-byte pieces of K (and of V) a thread holds per tile
+constexpr int kWaves = kBlock / 64;
+
+__device__ __forceinline__ float ninf() { return -__builtin_inff(); }
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Eq. 9 for one pair: sc[j] = (1/n) sum over the queued queries of their softmax row at mid
+// key j.  `g` is the pair's queue [n_rows][mid_n + 2] in global memory (logits in log2 units,
+// then the decode softmax's max and sum); `qs` is an LDS copy area of n_rows * (mid_n + 2)
+// floats and `st` LDS space for 2 * n_rows floats.  Mode 0 normalises each row over the mid
+// keys only; mode 1 uses the decode softmax's statistics.  All threads call it; it ends with
+// a barrier.  Sums run in a fixed order, so the result does not depend on timing.
+__device__ void block_saliency(const float* g, int n_rows, int line_len, int mid_n, int mode,
+                               float* qs, float* st, float* sc) {
+  const int tid = threadIdx.x;
+  const int pitch = mid_n + 2;
+  const int total = n_rows * pitch;
+  for (int i = tid; i < total; i += kBlock) qs[i] = g[i];
+  __syncthreads();
+  // Row statistics: a power-of-two team of threads per row.
+  int team = 1;
+  while (team < 16 && team * 2 * n_rows <= kBlock) team *= 2;
+  const int rows_per_pass = kBlock / team;
+  const int tr = tid / team, tq = tid % team;
+  for (int r0 = 0; r0 < n_rows; r0 += rows_per_pass) {
+    const int r = r0 + tr;
+    const bool on = r < n_rows;
+    const float* row = qs + (on ? r : 0) * pitch;
+    float mx, inv;
+    if (mode == 0) {
+      float lm = ninf();
+      for (int j = tq; j < mid_n; j += team) lm = fmaxf(lm, row[j]);
+      for (int o = team >> 1; o > 0; o >>= 1) lm = fmaxf(lm, __shfl_xor(lm, o));
+      float ls = 0.f;
+      for (int j = tq; j < mid_n; j += team) ls += ex2(row[j] - lm);
+      for (int o = team >> 1; o > 0; o >>= 1) ls += __shfl_xor(ls, o);
+      mx = lm;
+      inv = 1.0f / ls;
+    } else {
+      mx = row[mid_n];
+      inv = 1.0f / row[mid_n + 1];
+    }
+    if (on && tq == 0) {
+      st[2 * r] = mx;
+      st[2 * r + 1] = inv;
+    }
+  }
+  __syncthreads();
+  const float inv_n = 1.0f / (float)line_len;
+  for (int j = tid; j < mid_n; j += kBlock) {
+    float t = 0.f;
+    for (int r = 0; r < n_rows; ++r) t += ex2(qs[r * pitch + j] - st[2 * r]) * st[2 * r + 1];
+    sc[j] = t * inv_n;
+  }
+  __syncthreads();
+}
+
+// LDS floats block_saliency needs beyond sc[].
+__host__ __device__ inline size_t saliency_lds_words(int n_rows, int mid_n) {
+  return (size_t)n_rows * (mid_n + 2) + 2 * (size_t)n_rows;
+}
 
 template <int PPR>  // 16-byte pieces per key row
 __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   extern __shared__ int sm_raw[];
-  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] scores
-  int* keep = sm_raw + a.mid_n;                        // [mid_n] 1 = survives
-  int* src = sm_raw + 2 * a.mid_n;                     // [mid_n] source index of survivor slot
-  __shared__ int sm_first;
-
-  const int tid = threadIdx.x;
-  const int pair = blockIdx.x;
-  float* acc = a.acc + (size_t)pair * a.mid_n;
   const int m = a.mid_n;
+  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
+  int* src = sm_raw + m;                               // [mid_n] source index of survivor slot
+  float* qs = reinterpret_cast<float*>(sm_raw + 2 * m);
+  float* st = qs + (size_t)a.n_rows * (m + 2);
+  __shared__ int sm_first;
+  __shared__ unsigned long long sm_mask[kWaves];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int pair = blockIdx.x;
   const int mid_after = m - a.n_evict;
 
   if (tid == 0) sm_first = m;
-  for (int j = tid; j < m; j += kBlock) {
-    sc[j] = acc[j];
-    acc[j] = 0.f;                                      // next line starts from zero
-  }
-  __syncthreads();
-  // Eq. 10: rank = number of candidates that are evicted before this one.
-  for (int j = tid; j < m; j += kBlock) {
-    const float sj = sc[j];
-    int rank = 0;
-    for (int k = 0; k < m; ++k) {
-      const float sk = sc[k];
-      rank += (sk < sj) || (sk == sj && k < j);
+  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
+                 a.score_mode, qs, st, sc);
+  // Eq. 10: a candidate's rank is the number of candidates evicted before it (lower score,
+  // or equal score and older); the n lowest ranks go.  Survivors get their new slot from a
+  // prefix count over the keep flags, 256 candidates at a time.
+  int running = 0;
+  for (int base = 0; base < m; base += kBlock) {
+    const int j = base + tid;
+    bool kp = false;
+    if (j < m) {
+      const float sj = sc[j];
+      int rank = 0;
+      for (int k = 0; k < m; ++k) {
+        const float sk = sc[k];
+        rank += (sk < sj) || (sk == sj && k < j);
+      }
+      kp = rank >= a.n_evict;
+      if (!kp) atomicMin(&sm_first, j);
     }
-    const int kp = rank >= a.n_evict;
-    keep[j] = kp;
-    if (!kp) atomicMin(&sm_first, j);
-  }
-  __syncthreads();
-  for (int j = tid; j < m; j += kBlock) {
-    if (keep[j]) {
-      int dst = 0;
-      for (int k = 0; k < j; ++k) dst += keep[k];
-      src[dst] = j;
+    const unsigned long long mask = __ballot(kp);
+    if (lane == 0) sm_mask[wave] = mask;
+    __syncthreads();
+    int before = running, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const int c = __popcll(sm_mask[w]);
+      if (w < wave) before += c;
+      all += c;
     }
+    if (kp) src[before + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+    running += all;
+    __syncthreads();
   }
-  __syncthreads();
 
   // Destination rows [first, mid_after + n_tail), relative to mid_lo; rows in front of the
   // first hole stay where they are.
@@ -69,6 +140,7 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const int n_pieces = n_move * PPR;
   for (int t0 = 0; t0 < n_pieces; t0 += kTile) {
     uint4 kr[kPiecesPerThread], vr[kPiecesPerThread];
+    int32_t pr[kPiecesPerThread];
 #pragma unroll
     for (int i = 0; i < kPiecesPerThread; ++i) {
       const int piece = t0 + i * kBlock + tid;
@@ -77,6 +149,7 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
         const int s = d < mid_after ? src[d] : d + a.n_evict;
         kr[i] = kc[(size_t)s * PPR + c];
         vr[i] = vc[(size_t)s * PPR + c];
+        if (c == 0) pr[i] = pos[s];
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -88,18 +161,23 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
         const int d = first + piece / PPR, c = piece % PPR;
         kc[(size_t)d * PPR + c] = kr[i];
         vc[(size_t)d * PPR + c] = vr[i];
+        if (c == 0) pos[d] = pr[i];
       }
     }
   }
-  for (int t0 = 0; t0 < n_move; t0 += kBlock) {
-    const int d = first + t0 + tid;
-    int32_t p = 0;
-    const bool on = t0 + tid < n_move;
-    if (on) p = pos[d < mid_after ? src[d] : d + a.n_evict];
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (on) pos[d] = p;
-  }
+}
+
+// kv_scores: the saliency alone.
+__global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, float* out) {
+  extern __shared__ int sm_raw[];
+  const int m = a.mid_n;
+  float* sc = reinterpret_cast<float*>(sm_raw);
+  float* qs = sc + m;
+  float* st = qs + (size_t)a.n_rows * (m + 2);
+  const int pair = blockIdx.x;
+  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
+                 a.score_mode, qs, st, sc);
+  for (int j = threadIdx.x; j < m; j += kBlock) out[(size_t)pair * m + j] = sc[j];
 }
 
 __global__ __launch_bounds__(kBlock) void copy_rows_kernel(uint4* dst, int64_t dst_pitch,
@@ -145,12 +223,6 @@ __global__ __launch_bounds__(kBlock) void fill_u32_kernel(uint32_t* dst, uint32_
     dst[i] = v;
 }
 
-__global__ __launch_bounds__(kBlock) void scale_f32_kernel(float* out, const float* in, float f,
-                                                           size_t n) {
-  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
-    out[i] = in[i] * f;
-}
-
 unsigned grid_for(size_t n) {
   size_t g = (n + kBlock - 1) / kBlock;
   if (g > 4096) g = 4096;
@@ -162,7 +234,7 @@ unsigned grid_for(size_t n) {
 
 hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s) {
   const int row_bytes = head_dim * (dtype == 1 ? 2 : 4);
-  const size_t dyn = (size_t)a.mid_n * 3 * sizeof(int);
+  const size_t dyn = ((size_t)a.mid_n * 2 + saliency_lds_words(a.n_rows, a.mid_n)) * sizeof(int);
   const dim3 grid((unsigned)a.n_pairs), block(kBlock);
   switch (row_bytes / 16) {
     case 8: hipLaunchKernelGGL((evict_kernel<8>), grid, block, dyn, s, a); break;
@@ -170,6 +242,12 @@ hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t
     case 32: hipLaunchKernelGGL((evict_kernel<32>), grid, block, dyn, s, a); break;
     default: return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_saliency(const EvictArgs& a, float* out, hipStream_t s) {
+  const size_t dyn = ((size_t)a.mid_n + saliency_lds_words(a.n_rows, a.mid_n)) * sizeof(int);
+  hipLaunchKernelGGL(saliency_kernel, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out);
   return hipGetLastError();
 }
 
@@ -217,12 +295,6 @@ hipError_t launch_fill_u32(void* dst, uint32_t value, size_t n_words, hipStream_
   if (n_words == 0) return hipSuccess;
   hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(n_words)), dim3(kBlock), 0, s,
                      reinterpret_cast<uint32_t*>(dst), value, n_words);
-  return hipGetLastError();
-}
-
-hipError_t launch_scale_f32(float* out, const float* in, float f, size_t n, hipStream_t s) {
-  if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(scale_f32_kernel, dim3(grid_for(n)), dim3(kBlock), 0, s, out, in, f, n);
   return hipGetLastError();
 }
 

@@ -20,8 +20,9 @@ struct DecodeArgs {
   float* out;         // [P, d]
   float* part_o;      // [P, max_split, d]   split partial numerators
   float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
-  float* mid_logit;   // [P, mid_n]          logits of the mid keys when n_split > 1
-  float* acc;         // [P, mid_n]          running sum over the line's queries
+  float* guide;       // [P, n, mid_n + 2] guide queue of the layer, already advanced to this
+                      //                   query's row: mid logits (log2 units), then (m, l)
+  int64_t guide_pitch;  // floats between the rows of consecutive pairs = n * (mid_n + 2)
   int32_t n_pairs;    // P = Bz * H
   int32_t t;          // keys visible to this query, the new one included
   int32_t t_max;      // row pitch of the caches, in keys
@@ -37,12 +38,15 @@ struct DecodeArgs {
   float scale_log2e;  // logit scale times log2(e)
 };
 
-// End of line: BottomK over the accumulated saliency, then compaction (Eq. 5-7, 10).
+// End of line: saliency from the guide queue (Eq. 9), BottomK (Eq. 10), compaction (Eq. 5-7).
 struct EvictArgs {
   void* kc;
   void* vc;
   int32_t* pos;
-  float* acc;        // [P, mid_n], cleared on the way out
+  const float* guide;  // [P, n, mid_n + 2] of the layer
+  int32_t n_rows;      // queries queued in the line (n at an end of line)
+  int32_t line_len;    // n, the divisor of Eq. 9
+  int32_t score_mode;
   int32_t n_pairs;
   int32_t t_max;
   int32_t mid_lo;
@@ -56,6 +60,9 @@ int decode_rows_per_group(int dtype, int head_dim);   // keys one wave-wide load
 int decode_max_waves(int depth);                      // wavefronts per workgroup at that depth
 int decode_depth_for(int groups_per_wave);            // smallest instantiated depth >= the argument, 0 if none
 hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s);
+// out[P, mid_n] = saliency of Eq. 9 from the queue rows so far (uses guide, n_rows, line_len,
+// score_mode, n_pairs, mid_n of the arguments).
+hipError_t launch_saliency(const EvictArgs& a, float* out, hipStream_t s);
 
 // dst[p, 0:rows, :] = src[p, 0:rows, :] for p < n_pairs; pitches in rows; row_bytes % 16 == 0.
 hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,
@@ -71,7 +78,5 @@ hipError_t launch_iota_rows(int32_t* pos, int64_t pitch, int32_t rows, int32_t n
 hipError_t launch_copy_i32_rows(int32_t* dst, int64_t dst_pitch, const int32_t* src,
                                 int64_t src_pitch, int32_t rows, int32_t n_pairs, hipStream_t s);
 hipError_t launch_fill_u32(void* dst, uint32_t value, size_t n_words, hipStream_t s);
-// out[i] = in[i] * f
-hipError_t launch_scale_f32(float* out, const float* in, float f, size_t n, hipStream_t s);
 
 }  // namespace linear

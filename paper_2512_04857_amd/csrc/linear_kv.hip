@@ -17,7 +17,8 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-constexpr int kMaxMid = 4096;       // candidates the eviction kernel ranks in LDS
+constexpr int kMaxMid = 2048;       // candidates the eviction kernel ranks in LDS
+constexpr size_t kMaxEvictLds = 64 * 1024 - 64;
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -35,8 +36,9 @@ struct Derived {
   int max_split;    // pitch of the split-partial buffers
   float scale;
   // scratch layout (byte offsets)
-  size_t off_acc, off_pos, off_part_o, off_part_ml, off_mid, total;
-  size_t acc_layer, pos_layer;   // element strides per layer
+  size_t off_guide, off_pos, off_part_o, off_part_ml, total;
+  size_t guide_layer, pos_layer;   // element strides per layer
+  size_t guide_pair;               // floats of one pair's guide queue: n * (mid_n + 2)
 };
 
 int derive(const linear_cfg_t& c, Derived* d) {
@@ -63,18 +65,22 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->n_tail = c.n_recent_lines * c.line_len;
   d->mid_n = d->compresses ? c.budget - c.n_init - d->n_tail : 0;
   if (d->mid_n > kMaxMid) return LINEAR_EINVAL;
+  // The end-of-line kernel keeps the line's guide queue in LDS (64 KiB per workgroup).
+  if (d->compresses &&
+      ((size_t)c.line_len * (d->mid_n + 4) + 2 * (size_t)d->mid_n) * sizeof(float) > kMaxEvictLds)
+    return LINEAR_EINVAL;
   d->first_line = c.budget / c.line_len;
   d->max_split = linear::kMaxSplit;
   d->scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.head_dim);
   const size_t P = (size_t)d->pairs;
-  d->acc_layer = P * (size_t)d->mid_n;
+  d->guide_pair = d->compresses ? (size_t)c.line_len * (d->mid_n + 2) : 0;
+  d->guide_layer = P * d->guide_pair;
   d->pos_layer = P * (size_t)d->t_max;
   size_t off = 0;
-  d->off_acc = off;      off = align_up(off + d->acc_layer * c.n_layers * sizeof(float));
+  d->off_guide = off;    off = align_up(off + d->guide_layer * c.n_layers * sizeof(float));
   d->off_pos = off;      off = align_up(off + d->pos_layer * c.n_layers * sizeof(int32_t));
   d->off_part_o = off;   off = align_up(off + P * d->max_split * c.head_dim * sizeof(float));
   d->off_part_ml = off;  off = align_up(off + P * d->max_split * 2 * sizeof(float));
-  d->off_mid = off;      off = align_up(off + P * (size_t)d->mid_n * sizeof(float));
   d->total = off;
   return LINEAR_OK;
 }
@@ -211,8 +217,7 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
-  // Accumulators start at zero; position maps start with the prefix.
-  e = linear::launch_fill_u32(kv->scratch + d.off_acc, 0u, d.acc_layer * cfg->n_layers, s);
+  // Position maps start with the prefix; the guide queues are written before they are read.
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
     int32_t* pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * l;
     e = linear::launch_iota_rows(pos, d.t_max, cfg->n_cond, d.pairs, s);
@@ -260,8 +265,9 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.out = static_cast<float*>(out);
   a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
   a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
-  a.mid_logit = reinterpret_cast<float*>(kv->scratch + d.off_mid);
-  a.acc = reinterpret_cast<float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
+  a.guide = reinterpret_cast<float*>(kv->scratch + d.off_guide) + d.guide_layer * layer +
+            (size_t)ls.in_line * (d.mid_n + 2);
+  a.guide_pitch = (int64_t)d.guide_pair;
   a.n_pairs = d.pairs;
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
@@ -297,7 +303,10 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
     a.kc = kv->k_cache[layer];
     a.vc = kv->v_cache[layer];
     a.pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
-    a.acc = reinterpret_cast<float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
+    a.guide = reinterpret_cast<const float*>(kv->scratch + d.off_guide) + d.guide_layer * layer;
+    a.n_rows = c.line_len;
+    a.line_len = c.line_len;
+    a.score_mode = c.score_mode;
     a.n_pairs = d.pairs;
     a.t_max = d.t_max;
     a.mid_lo = d.mid_lo;
@@ -346,9 +355,14 @@ int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void
   const LayerState& ls = kv->layer[layer];
   if (ls.lines_done >= kv->cfg.n_lines || !line_evicts(*kv, ls.lines_done + 1)) return LINEAR_ESTATE;
   const Derived& d = kv->d;
-  const float* acc = reinterpret_cast<const float*>(kv->scratch + d.off_acc) + d.acc_layer * layer;
-  const hipError_t e = linear::launch_scale_f32(out, acc, 1.0f / (float)kv->cfg.line_len, d.acc_layer,
-                                                static_cast<hipStream_t>(stream));
+  linear::EvictArgs a = {};
+  a.guide = reinterpret_cast<const float*>(kv->scratch + d.off_guide) + d.guide_layer * layer;
+  a.n_rows = ls.in_line;
+  a.line_len = kv->cfg.line_len;
+  a.score_mode = kv->cfg.score_mode;
+  a.n_pairs = d.pairs;
+  a.mid_n = d.mid_n;
+  const hipError_t e = linear::launch_saliency(a, out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e);
   if (mid_out) *mid_out = d.mid_n;
   return LINEAR_OK;
