@@ -16,8 +16,11 @@
 //   * the new token is one extra row taken from the inputs; one wavefront counts it and
 //     writes it to the cache (Eq. 4);
 //   * on lines that end in an eviction the logits of the mid keys are appended to the line's
-//     guide queue (Eq. 8) through LDS; the softmax rows of Eq. 9 are evaluated once per line
-//     by the eviction kernel, so a decode step carries no reduction for them;
+//     guide queue (Eq. 8), staged through LDS so that they leave as one coalesced store; the
+//     softmax rows of Eq. 9 are evaluated once per line by the eviction kernel, so a decode
+//     step carries no reduction for them;
+//   * stores are few and early (the new row goes out right after the loads): a kernel this
+//     short pays for every store instruction and for the full latency of a late one;
 //   * a pair whose keys fit one workgroup (up to 144 row groups) is a single launch with
 //     no inter-workgroup traffic; longer ones are split over workgroups and merged by
 //     a second, tiny kernel (a kernel boundary is cheaper here than device-scope fences).
@@ -158,71 +161,88 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   const int pair = blockIdx.x, split = blockIdx.y;
   const int r0 = split * a.rows_per_split;               // cached rows [r0, r0 + n_rows)
   const int n_rows = min(a.t - 1, r0 + a.rows_per_split) - r0;
-  const int n_groups = (n_rows + RPW - 1) / RPW;
   const bool scoring = a.mid_n > 0;
-  // The appended token is counted by sub-group 0 of the wavefront with the fewest row groups
-  // of the last split.
-  const bool owner_wave = split == a.n_split - 1 && wave == n_groups % nw;
-  const bool owner = owner_wave && sub == 0;
+  // The appended token is counted by sub-group 0 of one wavefront of the last split (the
+  // host picks the one with the fewest row groups).
+  const bool owner = split == a.n_split - 1 && wave == a.new_wave && sub == 0;
 
   // ---- loads: straight-line, so that every later wait counts exactly the loads behind it.
-  // Row groups beyond the end re-read the last row (served by the caches) and are masked.
-  const uint4* kc = reinterpret_cast<const uint4*>(a.kc) + ((size_t)pair * a.t_max + r0) * LPR + seg;
-  const uint4* vc = reinterpret_cast<const uint4*>(a.vc) + ((size_t)pair * a.t_max + r0) * LPR + seg;
-  const uint4 qr = reinterpret_cast<const uint4*>(a.q)[(size_t)pair * LPR + seg];
-  const uint4 knr = reinterpret_cast<const uint4*>(a.k_new)[(size_t)pair * LPR + seg];
-  const uint4 vnr = reinterpret_cast<const uint4*>(a.v_new)[(size_t)pair * LPR + seg];
+  // Addresses are a uniform base plus a 32-bit lane offset.  Row groups beyond the end
+  // re-read the last row (served by the caches) and are masked.
+  constexpr unsigned kRowBytes = LPR * 16;
+  const char* kbase = static_cast<const char*>(a.kc) + ((size_t)pair * a.t_max + r0) * kRowBytes;
+  const char* vbase = static_cast<const char*>(a.vc) + ((size_t)pair * a.t_max + r0) * kRowBytes;
+  const unsigned in_off = (unsigned)seg * 16u;
+  const uint4 qr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.q) + (size_t)pair * kRowBytes + in_off);
+  const uint4 knr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.k_new) + (size_t)pair * kRowBytes + in_off);
+  const uint4 vnr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.v_new) + (size_t)pair * kRowBytes + in_off);
   uint4 kr[U], vr[U];
   int row[U];
-  const int last = max(n_rows - 1, 0);
+  unsigned off[U];
+  const unsigned last = (unsigned)max(n_rows - 1, 0);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     row[u] = (u * nw + wave) * RPW + sub;
-    kr[u] = kc[(unsigned)min(row[u], last) * LPR];
+    off[u] = min((unsigned)row[u], last) * kRowBytes + in_off;
+    kr[u] = *reinterpret_cast<const uint4*>(kbase + off[u]);
   }
+  __builtin_amdgcn_sched_barrier(0);   // all K requests go out before the first V request
 #pragma unroll
-  for (int u = 0; u < U; ++u) vr[u] = vc[(unsigned)min(row[u], last) * LPR];
+  for (int u = 0; u < U; ++u) vr[u] = *reinterpret_cast<const uint4*>(vbase + off[u]);
   // Nothing below may be scheduled in front of the loads: a wait placed between them would
   // hold back the rest of the requests for a full memory round trip.
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- logits in log2 units and this worker's maximum (Eq. 2, numerically shifted)
+  // Stores go out as early as their data exists: a kernel ends only when its last store has
+  // been acknowledged, so a store issued near the end adds its whole latency to the step.
+  if (owner) {
+    // Eq. 4: the new pair becomes row T-1 of the cache.
+    const size_t dst = ((size_t)pair * a.t_max + (a.t - 1)) * LPR + seg;
+    reinterpret_cast<uint4*>(a.kc)[dst] = knr;
+    reinterpret_cast<uint4*>(a.vc)[dst] = vnr;
+    if (seg == 0) a.pos[(size_t)pair * a.t_max + (a.t - 1)] = a.new_pos;
+  }
+  // ---- raw logits q.k and this worker's maximum (Eq. 2; the scale is applied with the shift)
   float s[U];
-  float s_new = sum_within<LPR>(E::dot(knr, qr)) * a.scale_log2e;
+  float s_new = sum_within<LPR>(E::dot(knr, qr));
   s_new = owner ? s_new : ninf();
   float m = s_new;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const float d = sum_within<LPR>(E::dot(kr[u], qr)) * a.scale_log2e;
+    const float d = sum_within<LPR>(E::dot(kr[u], qr));
     s[u] = row[u] < n_rows ? d : ninf();
     m = fmaxf(m, s[u]);
   }
+  const float c = a.scale_log2e;          // > 0: scaling commutes with the maximum
   if (scoring) {
-    // Eq. 8-9: the logits of the mid keys are staged in LDS (no vector-memory traffic while
-    // the V loads are in flight) and join the line's guide queue below.
+    // Eq. 8-9: the logits of the mid keys (log2 units) are staged in LDS: one 4-byte entry per
+    // key from a few lanes each would cost a vector-memory instruction per row group, and the
+    // memory system charges small scattered stores by the instruction.
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const unsigned j = (unsigned)(r0 + row[u] - a.mid_lo);
-      if (j < (unsigned)a.mid_n && seg == 0 && row[u] < n_rows) sm_mid[j] = s[u];
+      if (j < (unsigned)a.mid_n && seg == 0 && row[u] < n_rows) sm_mid[j] = s[u] * c;
     }
   }
   // ---- probabilities relative to the worker's own maximum, and its numerator
   const float m_ref = m > ninf() ? m : 0.f;
+  const float shift = -m_ref * c;
   float o[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) o[e] = 0.f;
-  float l = ex2(s_new - m_ref);            // exp2(-inf) = 0 where the row does not count
+  float l = ex2(__builtin_fmaf(s_new, c, shift));   // exp2(-inf) = 0 where the row does not count
   E::axpy(l, vnr, o);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const float p = ex2(s[u] - m_ref);
+    const float p = ex2(__builtin_fmaf(s[u], c, shift));
     l += p;
     E::axpy(p, vr[u], o);
   }
-  // ---- the wavefront's workers move to a common maximum and meet in LDS
-  const float m_wave = wave_max(m);
+  // ---- the wavefront's workers move to a common maximum (log2 units) and meet in LDS
+  const float m2 = m * c;
+  const float m_wave = wave_max(m2);
   {
-    const float f = m > ninf() ? ex2(m - m_wave) : 0.f;
+    const float f = m > ninf() ? ex2(m2 - m_wave) : 0.f;
     l *= f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) o[e] *= f;
@@ -233,17 +253,11 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     if (seg == 0) sm_l[worker] = l;
     if (lane == 0) sm_m[wave] = m_wave;
   }
-  if (owner) {
-    // Eq. 4: the new pair becomes row T-1 of the cache.
-    const size_t dst = ((size_t)pair * a.t_max + (a.t - 1)) * LPR + seg;
-    reinterpret_cast<uint4*>(a.kc)[dst] = knr;
-    reinterpret_cast<uint4*>(a.vc)[dst] = vnr;
-    if (seg == 0) a.pos[(size_t)pair * a.t_max + (a.t - 1)] = a.new_pos;
-  }
   __syncthreads();
   if (scoring && wave == nw - 1) {
-    // This workgroup's share of the query's guide-queue row, written by the last wavefront
-    // while the first one merges.
+    // This workgroup's share of the query's guide-queue row (Eq. 8) in one coalesced store,
+    // by the last wavefront while the first one merges; the softmax rows of Eq. 9 are
+    // evaluated once, at the end of the line.
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
     const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
     for (int j = j0 + lane; j < j1; j += 64) qrow[j] = sm_mid[j];

@@ -29,6 +29,7 @@ struct DecodeArgs {
   int32_t rows_per_split;  // cached keys per workgroup (a multiple of the row-group size)
   int32_t n_split;    // workgroups per pair
   int32_t n_waves;    // wavefronts per workgroup
+  int32_t new_wave;   // wavefront of the last split that counts the appended token
   int32_t depth;      // row groups a wavefront holds (an instantiated value, see decode_depth_for)
   int32_t max_split;  // pitch of the partial buffers
   int32_t mid_lo;     // first mid key (cache row index)

@@ -121,7 +121,7 @@ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // workgroup of up to decode_max_waves(depth) wavefronts holds a whole pair when it can
 // (one launch); longer caches, or too few pairs to fill 256 CUs, are split.
 struct Plan {
-  int n_split, rows_per_split, n_waves, depth;
+  int n_split, rows_per_split, n_waves, depth, new_wave;
 };
 
 bool make_plan(const linear_kv& kv, int cached_rows, Plan* p) {
@@ -156,6 +156,9 @@ bool make_plan(const linear_kv& kv, int cached_rows, Plan* p) {
       p->rows_per_split = gps * rpg;
       p->depth = depth;
       p->n_waves = nw;
+      // Row groups are dealt round-robin, so in the last split wavefront (groups % nw) is the
+      // first with one group fewer: it takes the appended token.
+      p->new_wave = (groups - (n_split - 1) * gps) % nw;
       return true;
     }
     nw = maxw;   // too many wavefronts for this depth: fewer, deeper ones
@@ -276,6 +279,7 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.n_split = plan.n_split;
   a.rows_per_split = plan.rows_per_split;
   a.n_waves = plan.n_waves;
+  a.new_wave = plan.new_wave;
   a.depth = plan.depth;
   a.max_split = d.max_split;
   a.mid_lo = d.mid_lo;
