@@ -218,7 +218,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="0 skips the CPU oracle leg")
     ap.add_argument("--skip-full", action="store_true", help="do not time the full-cache variant")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
-                    help="also run one plain device copy of this many MiB (a traffic yardstick for "
+                    help="also run one elementwise read+write pass over this many MiB (a traffic yardstick for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
     ap.add_argument("--n-split", type=int, default=0, help="decode kernel tuning (0 = automatic)")
@@ -251,9 +251,10 @@ def main():
         src = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=device).random_(0, 255)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst.copy_(src)
+        torch.add(src, 1, out=dst)      # an elementwise kernel (a plain copy_ may go to the DMA engines)
         torch.cuda.synchronize()
-        log(f"calibration copy: {args.calibrate_copy_mib} MiB read + {args.calibrate_copy_mib} MiB written")
+        log(f"calibration pass (uint8 add kernel): {args.calibrate_copy_mib} MiB read + "
+            f"{args.calibrate_copy_mib} MiB written")
         del src, dst
     comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split)
     log("compressed:", json.dumps(comp))

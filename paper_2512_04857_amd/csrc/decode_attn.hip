@@ -30,8 +30,16 @@ namespace linear {
 namespace {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
+// Results are written once and read by a later kernel: nontemporal stores keep them from
+// sitting dirty in L2 until the end-of-kernel write-back.
+__device__ __forceinline__ void store_nt(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_nt(int32_t* p, int32_t v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_nt(uint4* p, const uint4& v) {
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(p));
+}
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <int CTRL>
@@ -198,9 +206,9 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   if (owner) {
     // Eq. 4: the new pair becomes row T-1 of the cache.
     const size_t dst = ((size_t)pair * a.t_max + (a.t - 1)) * LPR + seg;
-    reinterpret_cast<uint4*>(a.kc)[dst] = knr;
-    reinterpret_cast<uint4*>(a.vc)[dst] = vnr;
-    if (seg == 0) a.pos[(size_t)pair * a.t_max + (a.t - 1)] = a.new_pos;
+    store_nt(&reinterpret_cast<uint4*>(a.kc)[dst], knr);
+    store_nt(&reinterpret_cast<uint4*>(a.vc)[dst], vnr);
+    if (seg == 0) store_nt(&a.pos[(size_t)pair * a.t_max + (a.t - 1)], a.new_pos);
   }
   // ---- raw logits q.k and this worker's maximum (Eq. 2; the scale is applied with the shift)
   float s[U];
@@ -260,7 +268,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     // evaluated once, at the end of the line.
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
     const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
-    for (int j = j0 + lane; j < j1; j += 64) qrow[j] = sm_mid[j];
+    for (int j = j0 + lane; j < j1; j += 64) store_nt(&qrow[j], sm_mid[j]);
   }
   if (wave != 0) return;
 
@@ -269,11 +277,11 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   if (a.n_split == 1) {
     const float inv = 1.0f / l_all;
 #pragma unroll
-    for (int c = 0; c < D / 64; ++c) a.out[(size_t)pair * D + c * 64 + lane] = o_all[c] * inv;
+    for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
     if (scoring && lane == 0) {   // the decode softmax's statistics, for score mode 1
       float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-      qrow[a.mid_n] = m_all;
-      qrow[a.mid_n + 1] = l_all;
+      store_nt(&qrow[a.mid_n], m_all);
+      store_nt(&qrow[a.mid_n + 1], l_all);
     }
     return;
   }
@@ -302,11 +310,11 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
   merge_partials<D, 1>(sm_m, sm_l, a.part_o + pbase * D, a.n_split, m_all, l_all, o_all);
   const float inv = 1.0f / l_all;
 #pragma unroll
-  for (int c = 0; c < D / 64; ++c) a.out[(size_t)pair * D + c * 64 + lane] = o_all[c] * inv;
+  for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
   if (a.mid_n > 0 && lane == 0) {
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-    qrow[a.mid_n] = m_all;
-    qrow[a.mid_n + 1] = l_all;
+    store_nt(&qrow[a.mid_n], m_all);
+    store_nt(&qrow[a.mid_n + 1], l_all);
   }
 }
 

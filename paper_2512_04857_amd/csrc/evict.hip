@@ -17,6 +17,7 @@ namespace {
 
 constexpr int kPiecesPerThread = 4;   // 16-byte pieces of K (and of V) a thread holds per tile
 constexpr int kWaves = kBlock / 64;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -159,9 +160,11 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
       const int piece = t0 + i * kBlock + tid;
       if (piece < n_pieces) {
         const int d = first + piece / PPR, c = piece % PPR;
-        kc[(size_t)d * PPR + c] = kr[i];
-        vc[(size_t)d * PPR + c] = vr[i];
-        if (c == 0) pos[d] = pr[i];
+        // Moved rows are next read by a later kernel: nontemporal stores (measured: the
+        // compaction's store phase takes 4 us instead of 10 at 1280 pairs).
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, kr[i]), reinterpret_cast<u32x4*>(&kc[(size_t)d * PPR + c]));
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, vr[i]), reinterpret_cast<u32x4*>(&vc[(size_t)d * PPR + c]));
+        if (c == 0) __builtin_nontemporal_store(pr[i], &pos[d]);
       }
     }
   }
