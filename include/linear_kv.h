@@ -146,9 +146,18 @@ LINEAR_API int kv_length(const linear_kv_t* kv, int32_t layer, int32_t* cached_t
  *                     take; fewer groups per wavefront = more wavefronts per pair; 0 = default;
  *   n_split         : workgroups the keys of one pair are split over, 1..64 (a split step
  *                     is two launches: partials, then merge); lowered for steps with too
- *                     few keys to give every workgroup one; 0 = automatic.
- * A shape that cannot hold a step's keys makes that decode_step return LINEAR_EINVAL. */
+ *                     few keys to give every workgroup one, raised for steps whose keys
+ *                     would not fit; 0 = automatic. */
 LINEAR_API int linear_set_tuning(linear_kv_t* kv, int32_t groups_per_wave, int32_t n_split);
+
+/* Host-only introspection of the decode kernel's launch shape for a step that sees
+ * `cached_keys` keys already in the cache (the appended one not counted), under the given
+ * tuning (0 = default): shape[0] = workgroups per (sequence, head) pair, shape[1] = cached
+ * keys per workgroup, shape[2] = wavefronts per workgroup, shape[3] = row groups a wavefront
+ * holds, shape[4] = the wavefront of the last workgroup that takes the appended token,
+ * shape[5] = keys per row group (one wave-wide 1 KiB load).  HOST pointers, no device work. */
+LINEAR_API int linear_plan_shape(const linear_cfg_t* cfg, int32_t cached_keys, int32_t groups_per_wave,
+                      int32_t n_split, int32_t* shape);
 
 /* Releases the handle (host memory only). */
 LINEAR_API int kv_free(linear_kv_t* kv);

@@ -18,7 +18,7 @@ LINEAR_F32, LINEAR_BF16 = 0, 1
 
 EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_layers",
            "end_of_line_evict", "end_of_line_evict_layers", "kv_scores",
-           "kv_gather", "kv_length", "linear_set_tuning", "kv_free", "linear_strerror",
+           "kv_gather", "kv_length", "linear_set_tuning", "linear_plan_shape", "kv_free", "linear_strerror",
            "linear_last_hip_error")
 
 
@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
         L.kv_gather.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
         L.kv_length.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         L.linear_set_tuning.argtypes = [vp, i32, i32]
+        L.linear_plan_shape.argtypes = [C.POINTER(LinearCfg), i32, i32, i32, C.POINTER(i32)]
         L.kv_free.argtypes = [vp]
         L.linear_strerror.argtypes = [C.c_int]
         L.linear_strerror.restype = C.c_char_p
@@ -157,6 +158,12 @@ def kv_length(kv: int, layer: int) -> tuple[int, int, int]:
 
 def linear_set_tuning(kv: int, groups_per_wave: int = 0, n_split: int = 0) -> None:
     _check(lib().linear_set_tuning(kv, groups_per_wave, n_split), "linear_set_tuning")
+
+
+def linear_plan_shape(cfg: LinearCfg, cached_keys: int, groups_per_wave: int = 0, n_split: int = 0) -> dict:
+    out = (C.c_int32 * 6)()
+    _check(lib().linear_plan_shape(C.byref(cfg), cached_keys, groups_per_wave, n_split, out), "linear_plan_shape")
+    return dict(zip(("n_split", "keys_per_workgroup", "n_waves", "depth", "new_wave", "keys_per_group"), out))
 
 
 def kv_free(kv: int) -> None:

@@ -106,13 +106,11 @@ struct linear_kv {
   std::vector<void*> k_cache, v_cache;
   char* scratch;
   std::vector<LayerState> layer;
-  int groups_per_wave;   // tuning: row groups a wavefront should take (1..16)
+  int groups_per_wave;   // tuning: row groups a wavefront should take (1..16), 0 = automatic
   int force_split;       // tuning: 0 = automatic
 };
 
 namespace {
-
-constexpr int kDefaultGroupsPerWave = 8;
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -124,19 +122,20 @@ struct Plan {
   int n_split, rows_per_split, n_waves, depth, new_wave;
 };
 
-bool make_plan(const linear_kv& kv, int cached_rows, Plan* p) {
-  const int rpg = linear::decode_rows_per_group(kv.cfg.dtype, kv.cfg.head_dim);
+bool make_plan(int dtype, int head_dim, int pairs, int target, int force_split, int cached_rows,
+               Plan* p) {
+  const int rpg = linear::decode_rows_per_group(dtype, head_dim);
   const int groups = ceil_div(cached_rows, rpg);
-  const int target = kv.groups_per_wave;
-  int n_split = kv.force_split;
+  int n_split = force_split;
   if (n_split == 0) {
     n_split = 1;
     if (groups > 144) n_split = ceil_div(groups, 128);
-    if (kv.d.pairs < 256 && groups >= 32) {   // few pairs: split to put ~256 workgroups in flight
-      const int want = std::min(ceil_div(256, kv.d.pairs), groups / 16);
+    if (pairs < 256 && groups >= 32) {   // few pairs: split to put ~256 workgroups in flight
+      const int want = std::min(ceil_div(256, pairs), groups / 16);
       n_split = std::max(n_split, want);
     }
   }
+  if (groups > 144 * n_split) n_split = ceil_div(groups, 128);   // a forced count that cannot hold the keys
   if (n_split > linear::kMaxSplit) return false;
   int gps = ceil_div(groups, n_split);                    // row groups per split
   while (n_split > 1 && (int64_t)(n_split - 1) * gps * rpg >= cached_rows) {   // no empty split
@@ -146,22 +145,34 @@ bool make_plan(const linear_kv& kv, int cached_rows, Plan* p) {
   if (gps < 1) gps = 1;
   // Wavefronts per workgroup: enough for `target` row groups each, at least as many as the
   // deepest kernel needs, at most what the register budget of the resulting depth allows.
-  int nw = std::min(16, std::max(ceil_div(gps, target), ceil_div(gps, 16)));
-  for (int tries = 0; tries < 4; ++tries) {
-    const int depth = linear::decode_depth_for(ceil_div(gps, nw));
-    if (depth == 0) return false;
-    const int maxw = linear::decode_max_waves(depth);
-    if (nw <= maxw) {
-      p->n_split = n_split;
-      p->rows_per_split = gps * rpg;
-      p->depth = depth;
-      p->n_waves = nw;
-      // Row groups are dealt round-robin, so in the last split wavefront (groups % nw) is the
-      // first with one group fewer: it takes the appended token.
-      p->new_wave = (groups - (n_split - 1) * gps) % nw;
-      return true;
-    }
-    nw = maxw;   // too many wavefronts for this depth: fewer, deeper ones
+  // Default shape (measured on all five workloads): the deepest wavefronts that still put
+  // about eight wavefronts on every compute unit; few, long wavefronts keep the per-wavefront
+  // prologue and merge small, but a launch with too few of them cannot cover the memory
+  // latency.
+  int nw;
+  if (target > 0) {
+    nw = std::max(ceil_div(gps, target), ceil_div(gps, 16));
+  } else {
+    const int want_total = 8 * 256;
+    nw = std::max(ceil_div(gps, 16), ceil_div(want_total, pairs * n_split));
+    nw = std::min(nw, gps);
+  }
+  nw = std::max(1, std::min(16, nw));
+  // The nearest wavefront count whose depth is instantiated and fits the register budget
+  // (first upwards, then downwards).
+  for (int k = 0; k < 32; ++k) {
+    const int cand = k < 17 - nw ? nw + k : nw - (k - (16 - nw));
+    if (cand < 1 || cand > 16) continue;
+    const int depth = linear::decode_depth_for(ceil_div(gps, cand));
+    if (depth == 0 || cand > linear::decode_max_waves(depth)) continue;
+    p->n_split = n_split;
+    p->rows_per_split = gps * rpg;
+    p->depth = depth;
+    p->n_waves = cand;
+    // Row groups are dealt round-robin, so in the last split wavefront (groups % nw) is the
+    // first with one group fewer: it takes the appended token.
+    p->new_wave = (groups - (n_split - 1) * gps) % cand;
+    return true;
   }
   return false;
 }
@@ -211,7 +222,7 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
     kv->v_cache.assign(v_cache, v_cache + cfg->n_layers);
     kv->scratch = static_cast<char*>(scratch);
     kv->layer.assign(cfg->n_layers, LayerState());
-    kv->groups_per_wave = kDefaultGroupsPerWave;
+    kv->groups_per_wave = 0;
     kv->force_split = 0;
   } catch (...) {   // host allocation failure must not cross the C boundary
     delete kv;
@@ -275,7 +286,8 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
   Plan plan;
-  if (!make_plan(*kv, a.t - 1, &plan)) return LINEAR_EINVAL;
+  if (!make_plan(c.dtype, c.head_dim, d.pairs, kv->groups_per_wave, kv->force_split, a.t - 1, &plan))
+    return LINEAR_EINVAL;
   a.n_split = plan.n_split;
   a.rows_per_split = plan.rows_per_split;
   a.n_waves = plan.n_waves;
@@ -411,8 +423,29 @@ int linear_set_tuning(linear_kv_t* kv, int32_t groups_per_wave, int32_t n_split)
   if (!kv) return LINEAR_ENULL;
   if (groups_per_wave < 0 || groups_per_wave > 16 || n_split < 0 || n_split > linear::kMaxSplit)
     return LINEAR_EINVAL;
-  kv->groups_per_wave = groups_per_wave ? groups_per_wave : kDefaultGroupsPerWave;
+  kv->groups_per_wave = groups_per_wave;
   kv->force_split = n_split;
+  return LINEAR_OK;
+}
+
+int linear_plan_shape(const linear_cfg_t* cfg, int32_t cached_keys, int32_t groups_per_wave,
+                      int32_t n_split, int32_t* shape) {
+  if (!cfg || !shape) return LINEAR_ENULL;
+  Derived d;
+  const int rc = derive(*cfg, &d);
+  if (rc != LINEAR_OK) return rc;
+  if (cached_keys < 0 || cached_keys >= d.t_max || groups_per_wave < 0 || groups_per_wave > 16 ||
+      n_split < 0 || n_split > linear::kMaxSplit)
+    return LINEAR_EINVAL;
+  Plan p;
+  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, groups_per_wave, n_split, cached_keys, &p))
+    return LINEAR_EINVAL;
+  shape[0] = p.n_split;
+  shape[1] = p.rows_per_split;
+  shape[2] = p.n_waves;
+  shape[3] = p.depth;
+  shape[4] = p.new_wave;
+  shape[5] = linear::decode_rows_per_group(cfg->dtype, cfg->head_dim);
   return LINEAR_OK;
 }
 

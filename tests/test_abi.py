@@ -87,3 +87,36 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "liblinear_kv.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.lib()
+
+
+DEPTHS = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16}
+
+
+@pytest.mark.parametrize("name", sorted(synth.WORKLOADS))
+@pytest.mark.parametrize("full", [False, True])
+def test_launch_shape_covers_every_step(name, full):
+    """Host planner: for every cache length a workload reaches (compressed and full cache),
+    the decode kernel's launch shape holds all cached keys, leaves no workgroup empty, uses an
+    instantiated depth within the register budget, and names a valid wavefront for the new
+    token."""
+    w = synth.WORKLOADS[name]
+    w = w.full_cache() if full else w
+    cfg = binding.cfg_from_workload(w)
+    t_max = w.n_cond + w.budget
+    for gpw, ns in ((0, 0), (1, 0), (5, 0), (16, 0), (0, 3), (3, 7)):
+        for keys in range(0, t_max):
+            p = binding.linear_plan_shape(cfg, keys, gpw, ns)
+            rpg = p["keys_per_group"]
+            assert p["keys_per_workgroup"] % rpg == 0
+            assert p["n_split"] * p["keys_per_workgroup"] >= keys
+            assert p["n_split"] == 1 or (p["n_split"] - 1) * p["keys_per_workgroup"] < keys
+            assert p["depth"] in DEPTHS
+            assert 1 <= p["n_waves"] <= (16 if p["depth"] <= 8 else 12 if p["depth"] <= 12 else 8)
+            assert p["n_waves"] * p["depth"] * rpg >= p["keys_per_workgroup"]
+            assert 0 <= p["new_wave"] < p["n_waves"]
+            if ns:
+                assert p["n_split"] <= max(ns, -(-keys // (128 * rpg)))
+            last = keys - (p["n_split"] - 1) * p["keys_per_workgroup"]
+            assert p["new_wave"] == -(-last // rpg) % p["n_waves"]
+    with pytest.raises(binding.LinearError):
+        binding.linear_plan_shape(cfg, t_max, 0, 0)
