@@ -16,7 +16,7 @@ namespace linear {
 namespace {
 
 constexpr int kPiecesPerThread = 4;   // 16-byte pieces of K (and of V) a thread holds per tile
-constexpr int kWaves = kBlock / 64;
+constexpr int kMaxWaves = 16;
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
@@ -30,15 +30,15 @@ __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x)
 // a barrier.  Sums run in a fixed order, so the result does not depend on timing.
 __device__ void block_saliency(const float* g, int n_rows, int line_len, int mid_n, int mode,
                                float* qs, float* st, float* sc) {
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, nthreads = blockDim.x;
   const int pitch = mid_n + 2;
   const int total = n_rows * pitch;
-  for (int i = tid; i < total; i += kBlock) qs[i] = g[i];
+  for (int i = tid; i < total; i += nthreads) qs[i] = g[i];
   __syncthreads();
   // Row statistics: a power-of-two team of threads per row.
   int team = 1;
-  while (team < 16 && team * 2 * n_rows <= kBlock) team *= 2;
-  const int rows_per_pass = kBlock / team;
+  while (team < 16 && team * 2 * n_rows <= nthreads) team *= 2;
+  const int rows_per_pass = nthreads / team;
   const int tr = tid / team, tq = tid % team;
   for (int r0 = 0; r0 < n_rows; r0 += rows_per_pass) {
     const int r = r0 + tr;
@@ -65,7 +65,7 @@ __device__ void block_saliency(const float* g, int n_rows, int line_len, int mid
   }
   __syncthreads();
   const float inv_n = 1.0f / (float)line_len;
-  for (int j = tid; j < mid_n; j += kBlock) {
+  for (int j = tid; j < mid_n; j += nthreads) {
     float t = 0.f;
     for (int r = 0; r < n_rows; ++r) t += ex2(qs[r * pitch + j] - st[2 * r]) * st[2 * r + 1];
     sc[j] = t * inv_n;
@@ -78,29 +78,18 @@ __host__ __device__ inline size_t saliency_lds_words(int n_rows, int mid_n) {
   return (size_t)n_rows * (mid_n + 2) + 2 * (size_t)n_rows;
 }
 
-template <int PPR>  // 16-byte pieces per key row
-__global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
-  extern __shared__ int sm_raw[];
-  const int m = a.mid_n;
-  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
-  int* src = sm_raw + m;                               // [mid_n] source index of survivor slot
-  float* qs = reinterpret_cast<float*>(sm_raw + 2 * m);
-  float* st = qs + (size_t)a.n_rows * (m + 2);
-  __shared__ int sm_first;
-  __shared__ unsigned long long sm_mask[kWaves];
-
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int pair = blockIdx.x;
-  const int mid_after = m - a.n_evict;
-
-  if (tid == 0) sm_first = m;
-  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
-                 a.score_mode, qs, st, sc);
-  // Eq. 10: a candidate's rank is the number of candidates evicted before it (lower score,
-  // or equal score and older); the n lowest ranks go.  Survivors get their new slot from a
-  // prefix count over the keep flags, 256 candidates at a time.
+// Eq. 10 for one pair: a candidate's rank is the number of candidates evicted before it
+// (lower score, or equal score and older); the n_evict lowest ranks go.  Survivors get their
+// new slot from a prefix count over the keep flags, one workgroup-width of candidates at a
+// time.  Writes src[new slot] = old index (if src) and dst[old index] = new slot or -1 (if
+// dst); *first receives the smallest evicted index (it must hold mid_n on entry).  All
+// threads call it; it ends with a barrier.
+__device__ void select_survivors(const float* sc, int m, int n_evict, int* src, int* dst, int* first,
+                                 unsigned long long* masks) {
+  const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, lane = tid & 63;
+  const int n_waves = nthreads >> 6;
   int running = 0;
-  for (int base = 0; base < m; base += kBlock) {
+  for (int base = 0; base < m; base += nthreads) {
     const int j = base + tid;
     bool kp = false;
     if (j < m) {
@@ -110,23 +99,47 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
         const float sk = sc[k];
         rank += (sk < sj) || (sk == sj && k < j);
       }
-      kp = rank >= a.n_evict;
-      if (!kp) atomicMin(&sm_first, j);
+      kp = rank >= n_evict;
+      if (!kp) atomicMin(first, j);
     }
     const unsigned long long mask = __ballot(kp);
-    if (lane == 0) sm_mask[wave] = mask;
+    if (lane == 0) masks[wave] = mask;
     __syncthreads();
     int before = running, all = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const int c = __popcll(sm_mask[w]);
+    for (int w = 0; w < n_waves; ++w) {
+      const int c = __popcll(masks[w]);
       if (w < wave) before += c;
       all += c;
     }
-    if (kp) src[before + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+    if (j < m) {
+      const int slot = before + __popcll(mask & ((1ull << lane) - 1ull));
+      if (kp && src) src[slot] = j;
+      if (dst) dst[j] = kp ? slot : -1;
+    }
     running += all;
     __syncthreads();
   }
+}
+
+template <int PPR>  // 16-byte pieces per key row
+__global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
+  extern __shared__ int sm_raw[];
+  const int m = a.mid_n;
+  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
+  int* src = sm_raw + m;                               // [mid_n] source index of survivor slot
+  float* qs = reinterpret_cast<float*>(sm_raw + 2 * m);
+  float* st = qs + (size_t)a.n_rows * (m + 2);
+  __shared__ int sm_first;
+  __shared__ unsigned long long sm_mask[kMaxWaves];
+
+  const int tid = threadIdx.x;
+  const int pair = blockIdx.x;
+  const int mid_after = m - a.n_evict;
+
+  if (tid == 0) sm_first = m;
+  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
+                 a.score_mode, qs, st, sc);
+  select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
 
   // Destination rows [first, mid_after + n_tail), relative to mid_lo; rows in front of the
   // first hole stay where they are.
@@ -162,6 +175,63 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
         const int d = first + piece / PPR, c = piece % PPR;
         // Moved rows are next read by a later kernel: nontemporal stores (measured: the
         // compaction's store phase takes 4 us instead of 10 at 1280 pairs).
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, kr[i]), reinterpret_cast<u32x4*>(&kc[(size_t)d * PPR + c]));
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, vr[i]), reinterpret_cast<u32x4*>(&vc[(size_t)d * PPR + c]));
+        if (c == 0) __builtin_nontemporal_store(pr[i], &pos[d]);
+      }
+    }
+  }
+}
+
+// The same end-of-line work when all rows that may move (the mid candidates and the r recent
+// lines) fit the workgroup's registers: they are requested first, so their memory latency
+// overlaps with the saliency and the selection, and they are written straight to their new
+// slots afterwards -- one memory round trip instead of one per tile, and no ordering hazard
+// at all because every source row has left memory before the first store.  Costs the read of
+// the n rows that end up evicted.
+template <int PPR, int PIECES, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
+  extern __shared__ int sm_raw[];
+  const int m = a.mid_n;
+  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
+  int* dstmap = sm_raw + m;                            // [mid_n] new slot, -1 = evicted
+  float* qs = reinterpret_cast<float*>(sm_raw + 2 * m);
+  float* st = qs + (size_t)a.n_rows * (m + 2);
+  __shared__ int sm_first;
+  __shared__ unsigned long long sm_mask[kMaxWaves];
+
+  const int tid = threadIdx.x;
+  const int pair = blockIdx.x;
+  const size_t row_base = (size_t)pair * a.t_max + a.mid_lo;
+  uint4* kc = reinterpret_cast<uint4*>(a.kc) + row_base * PPR;
+  uint4* vc = reinterpret_cast<uint4*>(a.vc) + row_base * PPR;
+  int32_t* pos = a.pos + row_base;
+  const int n_pieces = (m + a.n_tail) * PPR;           // host: <= BLOCK * PIECES
+
+  uint4 kr[PIECES], vr[PIECES];
+  int32_t pr[PIECES];
+#pragma unroll
+  for (int i = 0; i < PIECES; ++i) {
+    const int piece = i * BLOCK + tid;                 // rows are contiguous: piece = 16-byte index
+    if (piece < n_pieces) {
+      kr[i] = kc[piece];
+      vr[i] = vc[piece];
+      if (piece % PPR == 0) pr[i] = pos[piece / PPR];
+    }
+  }
+  if (tid == 0) sm_first = m;
+  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
+                 a.score_mode, qs, st, sc);
+  select_survivors(sc, m, a.n_evict, nullptr, dstmap, &sm_first, sm_mask);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();   // every row that may move is in registers
+#pragma unroll
+  for (int i = 0; i < PIECES; ++i) {
+    const int piece = i * BLOCK + tid;
+    if (piece < n_pieces) {
+      const int s = piece / PPR, c = piece % PPR;
+      const int d = s < m ? dstmap[s] : s - a.n_evict;
+      if (d >= 0 && d != s) {
         __builtin_nontemporal_store(__builtin_bit_cast(u32x4, kr[i]), reinterpret_cast<u32x4*>(&kc[(size_t)d * PPR + c]));
         __builtin_nontemporal_store(__builtin_bit_cast(u32x4, vr[i]), reinterpret_cast<u32x4*>(&vc[(size_t)d * PPR + c]));
         if (c == 0) __builtin_nontemporal_store(pr[i], &pos[d]);
@@ -235,17 +305,30 @@ unsigned grid_for(size_t n) {
 
 }  // namespace
 
+template <int PPR>
+hipError_t launch_evict_t(const EvictArgs& a, hipStream_t s) {
+  const size_t dyn = ((size_t)a.mid_n * 2 + saliency_lds_words(a.n_rows, a.mid_n)) * sizeof(int);
+  const dim3 grid((unsigned)a.n_pairs);
+  const int64_t pieces = (int64_t)(a.mid_n + a.n_tail) * PPR;
+  // Measured on the five workloads: with at least two pairs per compute unit the tiled
+  // kernel wins (it never reads the evicted rows); with fewer pairs than that and more than
+  // one tile of rows (Lumina: 256 pairs, 245 rows of 256 B) the register-resident kernel with
+  // 16 wavefronts per pair is 1.5x faster.
+  if (a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4)
+    hipLaunchKernelGGL((evict_fast_kernel<PPR, 4, 1024>), grid, dim3(1024), dyn, s, a);
+  else
+    hipLaunchKernelGGL((evict_kernel<PPR>), grid, dim3(kBlock), dyn, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s) {
   const int row_bytes = head_dim * (dtype == 1 ? 2 : 4);
-  const size_t dyn = ((size_t)a.mid_n * 2 + saliency_lds_words(a.n_rows, a.mid_n)) * sizeof(int);
-  const dim3 grid((unsigned)a.n_pairs), block(kBlock);
   switch (row_bytes / 16) {
-    case 8: hipLaunchKernelGGL((evict_kernel<8>), grid, block, dyn, s, a); break;
-    case 16: hipLaunchKernelGGL((evict_kernel<16>), grid, block, dyn, s, a); break;
-    case 32: hipLaunchKernelGGL((evict_kernel<32>), grid, block, dyn, s, a); break;
+    case 8: return launch_evict_t<8>(a, s);
+    case 16: return launch_evict_t<16>(a, s);
+    case 32: return launch_evict_t<32>(a, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_saliency(const EvictArgs& a, float* out, hipStream_t s) {

@@ -20,6 +20,9 @@ FULL_SPLIT = W("full-split", 1, 2, 3, 64, 3, 24, 12, 288, 24, 1, "bf16", 24)
 NO_COND = W("no-cond", 1, 1, 8, 64, 0, 8, 9, 32, 0, 1, "bf16", 25)
 F32_D64_LONG = W("f32-d64-long", 1, 1, 2, 64, 130, 16, 6, 64, 16, 1, "f32", 26)
 STREAMING = W("bf16-streaming", 1, 2, 2, 128, 7, 12, 6, 36, 12, 1, "bf16", 27)   # mid == n
+# 264 rows of 512 B may move at an end of line: more than the register-resident eviction
+# kernel holds, so this one runs the tiled kernel.
+F32_WIDE = W("f32-wide", 1, 1, 2, 128, 3, 64, 7, 320, 56, 1, "f32", 28)
 
 
 def say(msg):
@@ -48,7 +51,7 @@ def test_tiny_full_budget_never_evicts():
     (MID_SPLIT, 0, 3, 1), (LUMINA_SLICE, 0, 0, 0), (LUMINA_SLICE, 12, 1, 0), (LUMINA_SLICE, 4, 5, 0),
     (LUMINA_SLICE, 0, 2, 1), (F32_R2, 0, 0, 0), (F32_R2, 2, 2, 0), (FULL_SPLIT, 0, 0, 0),
     (FULL_SPLIT, 16, 1, 0), (FULL_SPLIT, 5, 3, 0), (NO_COND, 0, 0, 0), (NO_COND, 1, 0, 0),
-    (F32_D64_LONG, 0, 0, 0), (F32_D64_LONG, 8, 2, 1), (STREAMING, 0, 0, 0),
+    (F32_D64_LONG, 0, 0, 0), (F32_D64_LONG, 8, 2, 1), (STREAMING, 0, 0, 0), (F32_WIDE, 0, 0, 0),
 ], ids=lambda x: getattr(x, "name", str(x)))
 def test_mid_sizes_every_slice(w, gpw, n_split, score_mode):
     rep = run_parity(w, all_slices(w), groups_per_wave=gpw, n_split=n_split, score_mode=score_mode)
