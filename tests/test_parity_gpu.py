@@ -23,6 +23,8 @@ STREAMING = W("bf16-streaming", 1, 2, 2, 128, 7, 12, 6, 36, 12, 1, "bf16", 27)  
 # 264 rows of 512 B may move at an end of line: more than the register-resident eviction
 # kernel holds, so this one runs the tiled kernel.
 F32_WIDE = W("f32-wide", 1, 1, 2, 128, 3, 64, 7, 320, 56, 1, "f32", 28)
+ONE_TOKEN_LINES = W("one-token-lines", 1, 2, 2, 64, 2, 1, 12, 4, 1, 1, "bf16", 29)   # n = 1: evicts every step
+NO_ANCHOR_R3 = W("no-anchor-r3", 2, 1, 3, 64, 0, 6, 9, 36, 0, 3, "f32", 30)          # N_init = 0, r = 3
 
 
 def say(msg):
@@ -52,6 +54,7 @@ def test_tiny_full_budget_never_evicts():
     (LUMINA_SLICE, 0, 2, 1), (F32_R2, 0, 0, 0), (F32_R2, 2, 2, 0), (FULL_SPLIT, 0, 0, 0),
     (FULL_SPLIT, 16, 1, 0), (FULL_SPLIT, 5, 3, 0), (NO_COND, 0, 0, 0), (NO_COND, 1, 0, 0),
     (F32_D64_LONG, 0, 0, 0), (F32_D64_LONG, 8, 2, 1), (STREAMING, 0, 0, 0), (F32_WIDE, 0, 0, 0),
+    (ONE_TOKEN_LINES, 0, 0, 0), (ONE_TOKEN_LINES, 0, 0, 1), (NO_ANCHOR_R3, 0, 0, 0), (NO_ANCHOR_R3, 2, 2, 1),
 ], ids=lambda x: getattr(x, "name", str(x)))
 def test_mid_sizes_every_slice(w, gpw, n_split, score_mode):
     rep = run_parity(w, all_slices(w), groups_per_wave=gpw, n_split=n_split, score_mode=score_mode)
@@ -160,3 +163,105 @@ def test_repeatable_bit_for_bit():
         cache.close()
     for a, b in zip(*results):
         assert torch.equal(a, b)
+
+
+def test_scores_in_mid_line_and_gather_options():
+    """kv_scores before the line is complete returns the partial sum of Eq. 9 over the queries
+    queued so far (still divided by n); kv_gather accepts NULL outputs."""
+    import numpy as np
+    from parity_harness import oracle
+
+    o = oracle()
+    w = synth.shrink(synth.TINY_C, n_heads=2)
+    dev = "cuda:0"
+    cache = binding.LineARCache(binding.cfg_from_workload(w))
+    kc, vc = synth.cond_kv(w, dev)
+    cache.start_image(kc, vc)
+    out = torch.empty((w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
+    f64 = lambda t: t.to(torch.float64).cpu().numpy()
+    sl = [o.CacheSlice(f64(kc[0, 0, h]), f64(vc[0, 0, h]), line_len=w.line_len, n_lines=w.n_lines,
+                       budget=w.budget, n_init=w.n_init, n_recent_lines=w.n_recent_lines) for h in range(2)]
+    first_evicting_step = (w.budget // w.line_len - 1) * w.line_len
+    for step in range(first_evicting_step + 5):
+        q, k, v = synth.step_qkv(w, step, dev)
+        cache.decode_step(0, q[0], k[0], v[0], out)
+        for h in range(2):
+            sl[h].step(f64(q[0, 0, h]), f64(k[0, 0, h]), f64(v[0, 0, h]))
+        if (step + 1) % w.line_len == 0:
+            cache.end_of_line_evict(0)
+            for h in range(2):
+                sl[h].end_of_line()
+    got = cache.scores(0).cpu().numpy()             # 5 of 8 queries queued
+    for h in range(2):
+        lo, hi = sl[h].mid_range()
+        ref = o.saliency(np.stack(sl[h].guide_q), np.stack(sl[h].K[lo:hi]), sl[h].scale) * 5 / w.line_len
+        np.testing.assert_allclose(got[0, h], ref, rtol=1e-4, atol=1e-7)
+    n = binding.kv_gather(cache.handle, 0, 0, 0, 0)   # all outputs NULL: only the length
+    assert n == binding.kv_length(cache.handle, 0)[0] == w.n_cond + first_evicting_step + 5
+    pos = torch.empty((w.batch, w.n_heads, n), dtype=torch.int32, device=dev)
+    assert binding.kv_gather(cache.handle, 0, 0, 0, pos.data_ptr()) == n
+    assert pos[0, 0].tolist() == sl[0].pos
+    cache.close()
+
+
+def test_gather_then_resume_in_a_new_handle():
+    """Export of the retained cache and restart from it: a new handle primed with the gathered
+    rows as its conditional prefix continues with the same attention outputs (the exported
+    rows are exactly what the next steps attend to)."""
+    w = synth.Workload("resume", 1, 2, 3, 64, 4, 8, 8, 24, 4, 1, "bf16", 31)
+    dev = "cuda:0"
+    a = binding.LineARCache(binding.cfg_from_workload(w))
+    kc, vc = synth.cond_kv(w, dev)
+    a.start_image(kc, vc)
+    out = torch.empty((w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
+    stop = 5 * w.line_len                       # two evictions done
+    for step in range(stop):
+        q, k, v = synth.step_qkv(w, step, dev)
+        a.decode_step(0, q[0], k[0], v[0], out)
+        if (step + 1) % w.line_len == 0:
+            a.end_of_line_evict(0)
+    kg, vg, pg = a.gather(0)
+    assert kg.shape[2] == w.n_cond + w.budget - w.line_len
+    # continue in the original handle and, in parallel, in a full-cache handle whose prefix is
+    # the exported cache: until the next eviction both see the same keys.
+    w2 = synth.Workload("resume-b", 1, 2, 3, 64, kg.shape[2], 8, 1, 8, 0, 1, "bf16", 31)
+    b = binding.LineARCache(binding.cfg_from_workload(w2))
+    b.start_image(kg[None], vg[None])
+    out_b = torch.empty_like(out)
+    for step in range(stop, stop + w.line_len):
+        q, k, v = synth.step_qkv(w, step, dev)
+        a.decode_step(0, q[0], k[0], v[0], out)
+        b.decode_step(0, q[0], k[0], v[0], out_b)
+        assert torch.allclose(out, out_b, atol=2e-6, rtol=0), f"step {step}"
+    a.close()
+    b.close()
+
+
+def test_layers_entry_points_report_errors():
+    w = synth.shrink(synth.TINY_B, n_heads=2)
+    w = synth.Workload("two-layers", 2, 1, 2, 64, 8, 8, 8, 24, 4, 1, "f32", 32)
+    dev = "cuda:0"
+    cache = binding.LineARCache(binding.cfg_from_workload(w))
+    kc, vc = synth.cond_kv(w, dev)
+    cache.start_image(kc, vc)
+    q, k, v = synth.step_qkv(w, 0, dev)
+    out = torch.empty((w.n_layers, w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
+    stride, ostride = q[0].numel() * 4, out[0].numel() * 4
+    args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr())
+    with pytest.raises(binding.LinearError) as e:
+        binding.decode_step_layers(cache.handle, 1, 2, *args, stride, ostride)     # runs past the last layer
+    assert e.value.code == binding.LINEAR_EINVAL
+    with pytest.raises(binding.LinearError) as e:
+        binding.decode_step_layers(cache.handle, 0, 2, *args, stride + 4, ostride)  # stride not a multiple of 16
+    assert e.value.code == binding.LINEAR_EALIGN
+    with pytest.raises(binding.LinearError) as e:
+        binding.end_of_line_evict_layers(cache.handle, 0, 2)                      # line not complete
+    assert e.value.code == binding.LINEAR_ESTATE
+    assert binding.kv_length(cache.handle, 0) == (w.n_cond, 0, 0)
+    binding.decode_step_layers(cache.handle, 0, 0, *args, stride, ostride)         # count 0: nothing
+    for _ in range(w.line_len):
+        binding.decode_step_layers(cache.handle, 0, 2, *args, stride, ostride)
+    binding.end_of_line_evict_layers(cache.handle, 0, 2)
+    assert binding.kv_length(cache.handle, 1) == (w.n_cond + w.line_len, 0, 1)
+    torch.cuda.synchronize()
+    cache.close()
