@@ -265,7 +265,8 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   if (scoring && wave == nw - 1) {
     // This workgroup's share of the query's guide-queue row (Eq. 8) in one coalesced store,
     // by the last wavefront while the first one merges; the softmax rows of Eq. 9 are
-    // evaluated once, at the end of the line.
+    // evaluated once, at the end of the line.  (Issuing it earlier, behind a barrier of its
+    // own between the logits and the V phase, was measured slower.)
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
     const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
     for (int j = j0 + lane; j < j1; j += 64) store_nt(&qrow[j], sm_mid[j]);
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     const float inv = 1.0f / l_all;
 #pragma unroll
     for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
-    if (scoring && lane == 0) {   // the decode softmax's statistics, for score mode 1
+    if (scoring && a.score_mode == 1 && lane == 0) {   // the decode softmax's statistics
       float* qrow = a.guide + (size_t)pair * a.guide_pitch;
       store_nt(&qrow[a.mid_n], m_all);
       store_nt(&qrow[a.mid_n + 1], l_all);
@@ -311,7 +312,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
   const float inv = 1.0f / l_all;
 #pragma unroll
   for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
-  if (a.mid_n > 0 && lane == 0) {
+  if (a.mid_n > 0 && a.score_mode == 1 && lane == 0) {
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
     store_nt(&qrow[a.mid_n], m_all);
     store_nt(&qrow[a.mid_n + 1], l_all);
