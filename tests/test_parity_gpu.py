@@ -265,3 +265,16 @@ def test_layers_entry_points_report_errors():
     assert binding.kv_length(cache.handle, 1) == (w.n_cond + w.line_len, 0, 1)
     torch.cuda.synchronize()
     cache.close()
+
+
+def test_largest_mid_region():
+    """The largest mid region the end-of-line kernel accepts at n = 8 (1600 candidates: its LDS
+    copy of the guide queue is 64 KiB), with keys split over two workgroups: two evictions,
+    oracle on both heads."""
+    w = synth.Workload("largest-mid", 1, 1, 2, 64, 5, 8, 203, 1608, 0, 1, "bf16", 33)
+    rep = run_parity(w, all_slices(w), progress=None)
+    say(f"{w.name}: {rep}")
+    assert rep.evictions == 2 * 2 and rep.steps == w.n_visual
+    with pytest.raises(binding.LinearError):      # one more line of budget no longer fits
+        binding.linear_workspace_bytes(binding.cfg_from_workload(
+            synth.Workload("too-large-mid", 1, 1, 2, 64, 5, 8, 300, 1672, 0, 1, "bf16", 33)))
