@@ -24,17 +24,24 @@ __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x)
 
 // Eq. 9 for one pair: sc[j] = (1/n) sum over the queued queries of their softmax row at mid
 // key j.  `g` is the pair's queue [n_rows][mid_n + 2] in global memory (logits in log2 units,
-// then the decode softmax's max and sum); `qs` is an LDS copy area of n_rows * (mid_n + 2)
-// floats and `st` LDS space for 2 * n_rows floats.  Mode 0 normalises each row over the mid
+// then the decode softmax's max and sum); `qs_lds` is an LDS copy area of n_rows * (mid_n + 2)
+// floats, or nullptr when the queue is too large for LDS; `st` is LDS space for 2 * n_rows
+// floats.  Mode 0 normalises each row over the mid
 // keys only; mode 1 uses the decode softmax's statistics.  All threads call it; it ends with
 // a barrier.  Sums run in a fixed order, so the result does not depend on timing.
 __device__ void block_saliency(const float* g, int n_rows, int line_len, int mid_n, int mode,
-                               float* qs, float* st, float* sc) {
+                               float* qs_lds, float* st, float* sc) {
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int pitch = mid_n + 2;
   const int total = n_rows * pitch;
-  for (int i = tid; i < total; i += nthreads) qs[i] = g[i];
-  __syncthreads();
+  // The queue is read three times; it is copied to LDS when it fits (qs_lds != nullptr),
+  // otherwise the passes read it from global memory (it stays in L2).
+  const float* qs = g;
+  if (qs_lds) {
+    for (int i = tid; i < total; i += nthreads) qs_lds[i] = g[i];
+    qs = qs_lds;
+    __syncthreads();
+  }
   // Row statistics: a power-of-two team of threads per row.
   int team = 1;
   while (team < 16 && team * 2 * n_rows <= nthreads) team *= 2;
@@ -73,9 +80,15 @@ __device__ void block_saliency(const float* g, int n_rows, int line_len, int mid
   __syncthreads();
 }
 
-// LDS floats block_saliency needs beyond sc[].
-__host__ __device__ inline size_t saliency_lds_words(int n_rows, int mid_n) {
-  return (size_t)n_rows * (mid_n + 2) + 2 * (size_t)n_rows;
+// LDS words block_saliency needs beyond sc[]: the row statistics, and the queue copy when the
+// whole allocation stays within the 64 KiB every workgroup may use (`fixed_words` = what the
+// calling kernel keeps besides).
+constexpr size_t kLdsWords = (64 * 1024 - 256) / 4;
+inline bool queue_fits_lds(int n_rows, int mid_n, size_t fixed_words) {
+  return fixed_words + 2 * (size_t)n_rows + (size_t)n_rows * (mid_n + 2) <= kLdsWords;
+}
+inline size_t saliency_lds_words(int n_rows, int mid_n, size_t fixed_words) {
+  return 2 * (size_t)n_rows + (queue_fits_lds(n_rows, mid_n, fixed_words) ? (size_t)n_rows * (mid_n + 2) : 0);
 }
 
 // Eq. 10 for one pair: a candidate's rank is the number of candidates evicted before it
@@ -127,8 +140,8 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const int m = a.mid_n;
   float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
   int* src = sm_raw + m;                               // [mid_n] source index of survivor slot
-  float* qs = reinterpret_cast<float*>(sm_raw + 2 * m);
-  float* st = qs + (size_t)a.n_rows * (m + 2);
+  float* st = reinterpret_cast<float*>(sm_raw + 2 * m);   // [n_rows][2] row statistics
+  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr; // [n_rows][mid_n + 2] queue copy
   __shared__ int sm_first;
   __shared__ unsigned long long sm_mask[kMaxWaves];
 
@@ -195,8 +208,8 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
   const int m = a.mid_n;
   float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
   int* dstmap = sm_raw + m;                            // [mid_n] new slot, -1 = evicted
-  float* qs = reinterpret_cast<float*>(sm_raw + 2 * m);
-  float* st = qs + (size_t)a.n_rows * (m + 2);
+  float* st = reinterpret_cast<float*>(sm_raw + 2 * m);   // [n_rows][2] row statistics
+  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr; // [n_rows][mid_n + 2] queue copy
   __shared__ int sm_first;
   __shared__ unsigned long long sm_mask[kMaxWaves];
 
@@ -245,8 +258,8 @@ __global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, flo
   extern __shared__ int sm_raw[];
   const int m = a.mid_n;
   float* sc = reinterpret_cast<float*>(sm_raw);
-  float* qs = sc + m;
-  float* st = qs + (size_t)a.n_rows * (m + 2);
+  float* st = sc + m;
+  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr;
   const int pair = blockIdx.x;
   block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
                  a.score_mode, qs, st, sc);
@@ -306,8 +319,10 @@ unsigned grid_for(size_t n) {
 }  // namespace
 
 template <int PPR>
-hipError_t launch_evict_t(const EvictArgs& a, hipStream_t s) {
-  const size_t dyn = ((size_t)a.mid_n * 2 + saliency_lds_words(a.n_rows, a.mid_n)) * sizeof(int);
+hipError_t launch_evict_t(const EvictArgs& a0, hipStream_t s) {
+  EvictArgs a = a0;
+  a.queue_in_lds = queue_fits_lds(a.n_rows, a.mid_n, (size_t)a.mid_n * 2);
+  const size_t dyn = ((size_t)a.mid_n * 2 + saliency_lds_words(a.n_rows, a.mid_n, (size_t)a.mid_n * 2)) * sizeof(int);
   const dim3 grid((unsigned)a.n_pairs);
   const int64_t pieces = (int64_t)(a.mid_n + a.n_tail) * PPR;
   // Measured on the five workloads: with at least two pairs per compute unit the tiled
@@ -331,8 +346,10 @@ hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t
   }
 }
 
-hipError_t launch_saliency(const EvictArgs& a, float* out, hipStream_t s) {
-  const size_t dyn = ((size_t)a.mid_n + saliency_lds_words(a.n_rows, a.mid_n)) * sizeof(int);
+hipError_t launch_saliency(const EvictArgs& a0, float* out, hipStream_t s) {
+  EvictArgs a = a0;
+  a.queue_in_lds = queue_fits_lds(a.n_rows, a.mid_n, (size_t)a.mid_n);
+  const size_t dyn = ((size_t)a.mid_n + saliency_lds_words(a.n_rows, a.mid_n, (size_t)a.mid_n)) * sizeof(int);
   hipLaunchKernelGGL(saliency_kernel, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out);
   return hipGetLastError();
 }

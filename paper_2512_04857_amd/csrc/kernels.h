@@ -48,6 +48,7 @@ struct EvictArgs {
   int32_t n_rows;      // queries queued in the line (n at an end of line)
   int32_t line_len;    // n, the divisor of Eq. 9
   int32_t score_mode;
+  int32_t queue_in_lds;  // set by the launcher: the line's queue fits the workgroup's LDS
   int32_t n_pairs;
   int32_t t_max;
   int32_t mid_lo;

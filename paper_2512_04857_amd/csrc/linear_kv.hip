@@ -18,7 +18,7 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 constexpr int kMaxMid = 2048;       // candidates the eviction kernel ranks in LDS
-constexpr size_t kMaxEvictLds = 64 * 1024 - 64;
+constexpr int kMaxLine = 4096;      // guide queries whose row statistics it keeps in LDS
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -64,11 +64,7 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->mid_lo = c.n_cond + c.n_init;
   d->n_tail = c.n_recent_lines * c.line_len;
   d->mid_n = d->compresses ? c.budget - c.n_init - d->n_tail : 0;
-  if (d->mid_n > kMaxMid) return LINEAR_EINVAL;
-  // The end-of-line kernel keeps the line's guide queue in LDS (64 KiB per workgroup).
-  if (d->compresses &&
-      ((size_t)c.line_len * (d->mid_n + 4) + 2 * (size_t)d->mid_n) * sizeof(float) > kMaxEvictLds)
-    return LINEAR_EINVAL;
+  if (d->mid_n > kMaxMid || c.line_len > kMaxLine) return LINEAR_EINVAL;
   d->first_line = c.budget / c.line_len;
   d->max_split = linear::kMaxSplit;
   d->scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.head_dim);

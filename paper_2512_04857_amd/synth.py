@@ -72,9 +72,12 @@ LLAMAGEN_XL = _w("llamagen-xl", 36, 64, 20, 64, 1, 24, 24, 96, 24, 1, "bf16", 2)
 JANUS_PRO_1B = _w("janus-pro-1b", 24, 32, 16, 128, 64, 24, 24, 96, 24, 1, "bf16", 3)
 JANUS_PRO_7B = _w("janus-pro-7b", 30, 32, 32, 128, 128, 24, 24, 96, 24, 1, "bf16", 4)
 LUMINA_768 = _w("lumina-mgpt-768", 32, 8, 32, 128, 256, 49, 48, 294, 49, 1, "bf16", 5)
+# Beyond the five benchmark workloads: the paper's largest model (Table 1: N = 4160 = 64 lines of
+# 64 tokens + one end-of-line token, rho = 1/8, so B = 520 = 8 lines).
+LUMINA_1024 = _w("lumina-mgpt-1024", 32, 8, 32, 128, 256, 65, 64, 520, 65, 1, "bf16", 6)
 
 WORKLOADS = {w.name: w for w in (TINY_A, TINY_B, TINY_C, LLAMAGEN_XL, JANUS_PRO_1B,
-                                 JANUS_PRO_7B, LUMINA_768)}
+                                 JANUS_PRO_7B, LUMINA_768, LUMINA_1024)}
 
 
 def shrink(w: Workload, *, n_layers=None, batch=None, n_heads=None) -> Workload:

@@ -267,14 +267,26 @@ def test_layers_entry_points_report_errors():
     cache.close()
 
 
-def test_largest_mid_region():
-    """The largest mid region the end-of-line kernel accepts at n = 8 (1600 candidates: its LDS
-    copy of the guide queue is 64 KiB), with keys split over two workgroups: two evictions,
-    oracle on both heads."""
-    w = synth.Workload("largest-mid", 1, 1, 2, 64, 5, 8, 203, 1608, 0, 1, "bf16", 33)
+@pytest.mark.parametrize("budget,lines", [(1608, 203), (1672, 211)], ids=["queue-in-lds", "queue-in-l2"])
+def test_largest_mid_regions(budget, lines):
+    """Mid regions of 1600 candidates (at n = 8 the largest whose guide queue the end-of-line
+    kernel still copies to LDS) and of 1664 (read from global memory instead), with the keys
+    split over two workgroups: two evictions each, oracle on both heads."""
+    w = synth.Workload("largest-mid", 1, 1, 2, 64, 5, 8, lines, budget, 0, 1, "bf16", 33)
     rep = run_parity(w, all_slices(w), progress=None)
-    say(f"{w.name}: {rep}")
+    say(f"{w.name} B={budget}: {rep}")
     assert rep.evictions == 2 * 2 and rep.steps == w.n_visual
-    with pytest.raises(binding.LinearError):      # one more line of budget no longer fits
+    with pytest.raises(binding.LinearError):      # more than 2048 candidates are refused
         binding.linear_workspace_bytes(binding.cfg_from_workload(
-            synth.Workload("too-large-mid", 1, 1, 2, 64, 5, 8, 300, 1672, 0, 1, "bf16", 33)))
+            synth.Workload("too-large-mid", 1, 1, 2, 64, 5, 8, 400, 2072, 0, 1, "bf16", 33)))
+
+
+def test_lumina_1024_shape_sampled_slices():
+    """The paper's largest model shape (N = 4160, rho = 1/8; not one of the five benchmark
+    workloads): 520-key budget, 390 candidates per eviction, 56 evictions; its guide queue
+    (65 x 392 floats) does not fit LDS."""
+    w = synth.LUMINA_1024
+    sl = sampled_slices(w, [0, w.n_layers - 1], [w.batch - 1], [0, 13, 31])
+    rep = run_parity(w, sl, progress=say, layers_call=True)
+    say(f"{w.name}: {rep}")
+    assert rep.steps == w.n_visual and rep.evictions == 56 * len(sl)
