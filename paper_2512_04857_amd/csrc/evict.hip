@@ -331,6 +331,8 @@ hipError_t launch_evict_t(const EvictArgs& a0, hipStream_t s) {
   // 16 wavefronts per pair is 1.5x faster.
   if (a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4)
     hipLaunchKernelGGL((evict_fast_kernel<PPR, 4, 1024>), grid, dim3(1024), dyn, s, a);
+  else if (a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8)
+    hipLaunchKernelGGL((evict_fast_kernel<PPR, 8, 1024>), grid, dim3(1024), dyn, s, a);
   else
     hipLaunchKernelGGL((evict_kernel<PPR>), grid, dim3(kBlock), dyn, s, a);
   return hipGetLastError();
