@@ -226,10 +226,14 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     // Eq. 8-9: the logits of the mid keys (log2 units) are staged in LDS: one 4-byte entry per
     // key from a few lanes each would cost a vector-memory instruction per row group, and the
     // memory system charges small scattered stores by the instruction.
+    const int mid_first = a.mid_lo - r0, mid_end = min(mid_first + a.mid_n, n_rows);   // rows of this split
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const unsigned j = (unsigned)(r0 + row[u] - a.mid_lo);
-      if (j < (unsigned)a.mid_n && seg == 0 && row[u] < n_rows) sm_mid[j] = s[u] * c;
+      const int g0 = (u * nw + wave) * RPW;                     // wave-uniform: first row of the group
+      if (g0 < mid_end && g0 + RPW > mid_first) {
+        const int j = row[u] - mid_first;
+        if (seg == 0 && row[u] >= mid_first && row[u] < mid_end) sm_mid[j] = s[u] * c;
+      }
     }
   }
   // ---- probabilities relative to the worker's own maximum, and its numerator
