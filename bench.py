@@ -220,6 +220,9 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one elementwise read+write pass over this many MiB (a traffic yardstick for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
+    ap.add_argument("--sequences", type=int, default=0,
+                    help="override the number of sequences (e.g. 512 = the paper's Table 4 batch of 256 "
+                         "with both guidance halves, for the LlamaGen-XL shape)")
     ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
     ap.add_argument("--n-split", type=int, default=0, help="decode kernel tuning (0 = automatic)")
     args = ap.parse_args()
@@ -231,6 +234,9 @@ def main():
     from paper_2512_04857_amd import synth
 
     w = synth.WORKLOADS[args.workload]
+    if args.sequences:
+        from dataclasses import replace
+        w = replace(w, batch=args.sequences, name=f"{w.name}-seq{args.sequences}")
     steps = args.steps or w.n_visual
     if steps > w.n_visual:
         print(f"bench.py: --steps is capped at one image ({w.n_visual} decode steps)", file=sys.stderr)
