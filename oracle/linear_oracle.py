@@ -24,7 +24,12 @@ that matter here: conditional tokens are never evicted, never scored and do not
 count against B; N_init counts visual tokens; the softmax of Eq. 9 is over the
 mid columns only (score_mode 0) -- score_mode 1 instead takes each guide query's
 decode-time attention probabilities (softmax over the whole cache) restricted to
-mid; the first eviction happens at the end of line B/n, none after the last line;
+mid; score_mode 2 is the paper's "AttAcc" ablation (Sec. 4.4, Table 6: selection by
+accumulated attention inside the same pipeline), read the way it describes H2O
+(Sec. 4.2: "accumulated attention"): every cached token carries the sum of the
+decode-time probabilities it has received from every query since it was appended,
+its own included, the sum is never reset and travels with the token; the first
+eviction happens at the end of line B/n, none after the last line;
 BottomK breaks ties by evicting the older (smaller original position) token.
 
 Pins: every function below is pinned by tests/test_oracle_pins.py against
@@ -111,6 +116,7 @@ class CacheSlice:
         self.i = 0                   # visual tokens generated so far
         self.guide_q: list[np.ndarray] = []   # Eq. 8 queue (current line's queries)
         self.guide_p: list[np.ndarray] = []   # score_mode 1: their decode probabilities on mid
+        self.acc = [0.0] * self.C             # score_mode 2: attention received so far, per entry
         self.pending_eol = False
 
     # -- bookkeeping the paper states in prose --------------------------------
@@ -152,6 +158,10 @@ class CacheSlice:
         logits = (Kmat @ q) * self.scale
         p = softmax(logits)
         out = p @ Vmat
+        self.acc.append(0.0)
+        if self.score_mode == 2:
+            for j in range(len(self.acc)):
+                self.acc[j] += float(p[j])
         if self.line_evicts(self.line):
             self.guide_q.append(q)
             lo, hi = self.mid_range()
@@ -166,6 +176,8 @@ class CacheSlice:
         lo, hi = self.mid_range()
         if self.score_mode == 0:
             return saliency(np.stack(self.guide_q), np.stack(self.K[lo:hi]), self.scale)
+        if self.score_mode == 2:
+            return np.asarray(self.acc[lo:hi], dtype=F)
         return np.stack(self.guide_p).sum(axis=0) / len(self.guide_p)
 
     def end_of_line(self, force_evict_positions=None) -> dict | None:
@@ -204,6 +216,7 @@ class CacheSlice:
         self.pos = [self.pos[j] for j in keep]
         self.K = [self.K[j] for j in keep]
         self.V = [self.V[j] for j in keep]
+        self.acc = [self.acc[j] for j in keep]
         assert self.visual_len == self.B - self.n          # Eq. 6
         self.guide_q, self.guide_p = [], []
         return rec

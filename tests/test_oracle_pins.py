@@ -307,6 +307,39 @@ def pin_score_mode_1(o):
                 acc = None
 
 
+def pin_score_mode_2(o):
+    """score_mode 2 (accumulated attention): at every eviction the score of a mid token is
+    the sum, over every step since it was appended, of the probability it received -- here
+    recomputed from the raw history with a dictionary keyed by original position."""
+    for w in (synth.shrink(synth.TINY_C, n_heads=1), SMALL_R2):
+        kc, vc, Q, K, V = slice_inputs(w)
+        Kall = np.concatenate([kc, K])
+        sl = o.CacheSlice(kc, vc, score_mode=2, **cfg_of(w))
+        n, C = w.line_len, w.n_cond
+        sc = 1.0 / math.sqrt(w.head_dim)
+        received = {}
+        evictions = 0
+        for i in range(1, w.n_visual + 1):
+            visible = list(sl.pos) + [C + i - 1]
+            sl.step(Q[i - 1], K[i - 1], V[i - 1])
+            lg = Kall[visible] @ Q[i - 1] * sc
+            p = np.exp(lg - lg.max())
+            p /= p.sum()
+            for pos, pj in zip(visible, p):
+                received[pos] = received.get(pos, 0.0) + float(pj)
+            if i % n == 0:
+                r = sl.end_of_line()
+                if r is not None:
+                    evictions += 1
+                    want = np.array([received[pos] for pos in r["mid_positions"]])
+                    np.testing.assert_allclose(r["scores"], want, rtol=1e-12)
+                    order = np.argsort(want, kind="stable")[:n]
+                    assert sorted(np.array(r["mid_positions"])[order].tolist()) == r["evicted_positions"]
+        assert evictions == w.n_lines - w.budget // n
+        # total attention handed out = one unit per step
+        np.testing.assert_allclose(sum(received.values()), w.n_visual, rtol=1e-12)
+
+
 def pin_table4_budgets(o):
     """B = rho N as printed in Table 4, and n | B for the line lengths used
     (24 for N = 576; 49 = 48 + one end-of-line token for N = 2352)."""
@@ -398,6 +431,10 @@ MUTANTS = [
      "self.V = self.V[:len(keep)]"),
     ("mode 1 uses mid-only softmax", "self.guide_p.append(p[lo:hi].copy())",
      "self.guide_p.append(softmax(logits[lo:hi]))"),
+    ("mode 2 forgets the token's own step", "        self.acc.append(0.0)\n        if self.score_mode == 2:\n            for j in range(len(self.acc)):",
+     "        self.acc.append(0.0)\n        if self.score_mode == 2:\n            for j in range(len(self.acc) - 1):"),
+    ("mode 2 accumulators not compacted", "        self.acc = [self.acc[j] for j in keep]\n", "        self.acc = self.acc[:len(keep)]\n"),
+    ("mode 2 accumulates logits", "                self.acc[j] += float(p[j])", "                self.acc[j] += float(logits[j])"),
     ("gap uses wrong order statistics", "return float((s[k] - s[k - 1]) / s[k])",
      "return float((s[k + 1] - s[k]) / s[k + 1])"),
 ]
