@@ -95,12 +95,12 @@ class Runner:
         self.stride = self.q[0, 0].numel() * self.q.element_size()
         self.ostride = self.out[0].numel() * 4
 
-    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0):
+    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0, score_mode=0):
         """Times `steps` decode steps of workload variant `wl` (same shapes, its own budget)
         from the start of an image.  Returns a dict of measurements."""
         torch, binding = self.torch, self.binding
         L, n = wl.n_layers, wl.line_len
-        cache = binding.LineARCache(binding.cfg_from_workload(wl), self.device)
+        cache = binding.LineARCache(binding.cfg_from_workload(wl, score_mode=score_mode), self.device)
         lib = binding.lib()
         dsteps, evicts = lib.decode_step_layers, lib.end_of_line_evict_layers
         qb, kb, vb, ob = self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(), self.out.data_ptr()
@@ -223,6 +223,8 @@ def main():
     ap.add_argument("--sequences", type=int, default=0,
                     help="override the number of sequences (e.g. 512 = the paper's Table 4 batch of 256 "
                          "with both guidance halves, for the LlamaGen-XL shape)")
+    ap.add_argument("--score-mode", type=int, default=0,
+                    help="0 = Eq. 9 as printed (default), 1 = decode-softmax mass, 2 = accumulated attention")
     ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
     ap.add_argument("--n-split", type=int, default=0, help="decode kernel tuning (0 = automatic)")
     args = ap.parse_args()
@@ -262,7 +264,7 @@ def main():
         log(f"calibration pass (uint8 add kernel): {args.calibrate_copy_mib} MiB read + "
             f"{args.calibrate_copy_mib} MiB written")
         del src, dst
-    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split)
+    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split, args.score_mode)
     log("compressed:", json.dumps(comp))
     full = None if args.skip_full else r.run(w.full_cache(), steps, args.warmup, args.groups_per_wave, args.n_split)
     if full:
@@ -285,6 +287,7 @@ def main():
         "config": {"workload": w.name, "n_layers": w.n_layers, "sequences": w.batch, "n_heads": w.n_heads,
                    "head_dim": w.head_dim, "n_cond": w.n_cond, "grid": f"{w.n_lines}x{w.line_len}",
                    "budget": w.budget, "n_init": w.n_init, "n_recent_lines": w.n_recent_lines,
+                   "score_mode": args.score_mode,
                    "launches": "one decode kernel per layer per token, one eviction kernel per layer per line, "
                                "enqueued back to back on one stream (decode_step_layers), no graph"},
         "whole_image_ms": round(comp["total_ms"], 3) if steps == w.n_visual else None,

@@ -66,7 +66,11 @@ typedef struct {
   int32_t dtype;          /* LINEAR_F32 or LINEAR_BF16: q, k, v and both caches       */
   int32_t score_mode;     /* 0: Eq. 9 as printed, softmax over the mid tokens only;
                              1: each query's decode-time probabilities (softmax over
-                                everything it attends to) restricted to mid           */
+                                everything it attends to) restricted to mid;
+                             2: accumulated attention (the paper's AttAcc ablation, Table 6):
+                                every token behind the anchor carries the sum of the
+                                decode-time probabilities it received from every query since
+                                it was appended, never reset; needs B - N_init <= 8192    */
   float scale;            /* logit scale; 0 selects 1/sqrt(d) (Eq. 2)                 */
 } linear_cfg_t;
 
@@ -112,9 +116,10 @@ LINEAR_API int decode_step_layers(linear_kv_t* kv, int32_t first_layer, int32_t 
 
 /* End of a raster line of one layer (Sec. 3.3; Eq. 5-7 and 10).  Must follow exactly n
  * decode_step calls.  On lines B/n .. h-1 it evicts, independently per (sequence, head),
- * the n mid tokens with the smallest saliency (ties: older token first), compacts K, V and
- * the position map in place keeping ascending original position, and clears the
- * accumulator; on other lines it only advances the line counter.
+ * the n mid tokens with the smallest saliency (ties: older token first) and compacts K, V and
+ * the position map in place keeping ascending original position; on other lines it only
+ * advances the line counter (with score_mode 2 it also folds the line's attention into the
+ * per-token accumulators).
  * LINEAR_ESTATE in the middle of a line. */
 LINEAR_API int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream);
 
@@ -123,7 +128,7 @@ LINEAR_API int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, in
 
 /* Saliency of the current line so far (Eq. 9): S[j] for the mid candidates, averaged over
  * the n queries of the line (meaningful after the n-th decode_step of an evicting line,
- * before end_of_line_evict).  out: DEVICE [Bz, H, mid] float with
+ * before end_of_line_evict); with score_mode 2 the attention accumulated so far.  out: DEVICE [Bz, H, mid] float with
  * mid = B - N_init - r n; *mid_out (HOST, may be NULL) receives mid.
  * LINEAR_ESTATE if the layer's current line does not evict. */
 LINEAR_API int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void* stream);

@@ -235,6 +235,8 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
         if (seg == 0 && row[u] >= mid_first && row[u] < mid_end) sm_mid[j] = s[u] * c;
       }
     }
+    // accumulated attention also scores the appended token (row T-1) under its own query
+    if (a.stage_new && owner && seg == 0 && a.t - 1 >= a.mid_lo) sm_mid[a.t - 1 - a.mid_lo] = s_new * c;
   }
   // ---- probabilities relative to the worker's own maximum, and its numerator
   const float m_ref = m > ninf() ? m : 0.f;
@@ -272,7 +274,8 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     // evaluated once, at the end of the line.  (Issuing it earlier, behind a barrier of its
     // own between the logits and the V phase, was measured slower.)
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-    const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows - a.mid_lo, a.mid_n);
+    const int extra = a.stage_new && split == a.n_split - 1 ? 1 : 0;   // the appended token's entry
+    const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows + extra - a.mid_lo, a.mid_n);
     for (int j = j0 + lane; j < j1; j += 64) store_nt(&qrow[j], sm_mid[j]);
   }
   if (wave != 0) return;
@@ -283,10 +286,10 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     const float inv = 1.0f / l_all;
 #pragma unroll
     for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
-    if (scoring && a.score_mode == 1 && lane == 0) {   // the decode softmax's statistics
+    if (scoring && a.store_ml && lane == 0) {   // the decode softmax's statistics
       float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-      store_nt(&qrow[a.mid_n], m_all);
-      store_nt(&qrow[a.mid_n + 1], l_all);
+      store_nt(&qrow[a.guide_w], m_all);
+      store_nt(&qrow[a.guide_w + 1], l_all);
     }
     return;
   }
@@ -316,10 +319,10 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
   const float inv = 1.0f / l_all;
 #pragma unroll
   for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
-  if (a.mid_n > 0 && a.score_mode == 1 && lane == 0) {
+  if (a.mid_n > 0 && a.store_ml && lane == 0) {
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-    store_nt(&qrow[a.mid_n], m_all);
-    store_nt(&qrow[a.mid_n + 1], l_all);
+    store_nt(&qrow[a.guide_w], m_all);
+    store_nt(&qrow[a.guide_w + 1], l_all);
   }
 }
 

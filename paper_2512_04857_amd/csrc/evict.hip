@@ -22,20 +22,23 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Eq. 9 for one pair: sc[j] = (1/n) sum over the queued queries of their softmax row at mid
-// key j.  `g` is the pair's queue [n_rows][mid_n + 2] in global memory (logits in log2 units,
-// then the decode softmax's max and sum); `qs_lds` is an LDS copy area of n_rows * (mid_n + 2)
-// floats, or nullptr when the queue is too large for LDS; `st` is LDS space for 2 * n_rows
-// floats.  Mode 0 normalises each row over the mid
-// keys only; mode 1 uses the decode softmax's statistics.  All threads call it; it ends with
-// a barrier.  Sums run in a fixed order, so the result does not depend on timing.
-__device__ void block_saliency(const float* g, int n_rows, int line_len, int mid_n, int mode,
-                               float* qs_lds, float* st, float* sc) {
+// Column sums of the line's softmax rows for one pair.
+//   modes 0, 1 (Eq. 9): sc[j] = (1/n) sum over the queued queries of their softmax row at mid
+//     key j; mode 0 normalises each row over the mid keys only, mode 1 uses the decode
+//     softmax's (max, sum) stored behind the row's logits;
+//   mode 2 (accumulated attention): sc[j] = sum over the queued queries of the decode-time
+//     probability of scored key j; row r scores len0 + r * len_step keys (the line grows), the
+//     rest of the row is not read.
+// `g` is the pair's queue [n_rows][guide_w + 2] in global memory (logits in log2 units);
+// `qs_lds` is an LDS copy area of n_rows * (guide_w + 2) floats, or nullptr when the queue is
+// too large for LDS (then the three passes read global memory, where it stays in L2); `st` is
+// LDS space for 2 * n_rows floats.  All threads call it; it ends with a barrier.  Sums run in
+// a fixed order, so the result does not depend on timing.
+__device__ void block_saliency(const EvictArgs& a, const float* g, float* qs_lds, float* st, float* sc) {
   const int tid = threadIdx.x, nthreads = blockDim.x;
-  const int pitch = mid_n + 2;
+  const int n_rows = a.n_rows, mode = a.score_mode;
+  const int pitch = a.guide_w + 2;
   const int total = n_rows * pitch;
-  // The queue is read three times; it is copied to LDS when it fits (qs_lds != nullptr),
-  // otherwise the passes read it from global memory (it stays in L2).
   const float* qs = g;
   if (qs_lds) {
     for (int i = tid; i < total; i += nthreads) qs_lds[i] = g[i];
@@ -53,17 +56,18 @@ __device__ void block_saliency(const float* g, int n_rows, int line_len, int mid
     const float* row = qs + (on ? r : 0) * pitch;
     float mx, inv;
     if (mode == 0) {
+      const int len = a.len0;
       float lm = ninf();
-      for (int j = tq; j < mid_n; j += team) lm = fmaxf(lm, row[j]);
+      for (int j = tq; j < len; j += team) lm = fmaxf(lm, row[j]);
       for (int o = team >> 1; o > 0; o >>= 1) lm = fmaxf(lm, __shfl_xor(lm, o));
       float ls = 0.f;
-      for (int j = tq; j < mid_n; j += team) ls += ex2(row[j] - lm);
+      for (int j = tq; j < len; j += team) ls += ex2(row[j] - lm);
       for (int o = team >> 1; o > 0; o >>= 1) ls += __shfl_xor(ls, o);
       mx = lm;
       inv = 1.0f / ls;
     } else {
-      mx = row[mid_n];
-      inv = 1.0f / row[mid_n + 1];
+      mx = row[a.guide_w];
+      inv = 1.0f / row[a.guide_w + 1];
     }
     if (on && tq == 0) {
       st[2 * r] = mx;
@@ -71,24 +75,46 @@ __device__ void block_saliency(const float* g, int n_rows, int line_len, int mid
     }
   }
   __syncthreads();
-  const float inv_n = 1.0f / (float)line_len;
-  for (int j = tid; j < mid_n; j += nthreads) {
+  const float weight = mode == 2 ? 1.0f : 1.0f / (float)a.line_len;
+  for (int j = tid; j < a.n_cols; j += nthreads) {
     float t = 0.f;
-    for (int r = 0; r < n_rows; ++r) t += ex2(qs[r * pitch + j] - st[2 * r]) * st[2 * r + 1];
-    sc[j] = t * inv_n;
+    // rows whose scored length does not reach column j come first (lengths grow with r)
+    int r_first = 0;
+    if (a.len_step > 0 && j >= a.len0) r_first = (j - a.len0) / a.len_step + 1;
+    else if (a.len_step == 0 && j >= a.len0) r_first = n_rows;
+    for (int r = r_first; r < n_rows; ++r) t += ex2(qs[r * pitch + j] - st[2 * r]) * st[2 * r + 1];
+    sc[j] = t * weight;
   }
   __syncthreads();
+}
+
+// Mode 2: adds the pair's accumulators to the line's column sums; sc[0 .. n_cols) becomes the
+// attention each scored slot has received so far, slots beyond n_cols read as zero.  Ends with
+// a barrier.
+__device__ void add_accumulated(const EvictArgs& a, int pair, float* sc) {
+  const float* acc = a.acc + (size_t)pair * a.guide_w;
+  for (int j = threadIdx.x; j < a.guide_w; j += blockDim.x) sc[j] = j < a.n_cols ? sc[j] + acc[j] : 0.f;
+  __syncthreads();
+}
+
+// Mode 2, after a selection: the accumulators move with their tokens (survivors of mid, then
+// everything behind mid n_evict slots down); the freed slots start from zero.
+__device__ void compact_accumulated(const EvictArgs& a, int pair, const float* sc, const int* src) {
+  float* acc = a.acc + (size_t)pair * a.guide_w;
+  const int mid_after = a.mid_n - a.n_evict, moved = a.guide_w - a.n_evict;
+  for (int d = threadIdx.x; d < a.guide_w; d += blockDim.x)
+    acc[d] = d < mid_after ? sc[src[d]] : (d < moved ? sc[d + a.n_evict] : 0.f);
 }
 
 // LDS words block_saliency needs beyond sc[]: the row statistics, and the queue copy when the
 // whole allocation stays within the 64 KiB every workgroup may use (`fixed_words` = what the
 // calling kernel keeps besides).
 constexpr size_t kLdsWords = (64 * 1024 - 256) / 4;
-inline bool queue_fits_lds(int n_rows, int mid_n, size_t fixed_words) {
-  return fixed_words + 2 * (size_t)n_rows + (size_t)n_rows * (mid_n + 2) <= kLdsWords;
+inline bool queue_fits_lds(int n_rows, int guide_w, size_t fixed_words) {
+  return fixed_words + 2 * (size_t)n_rows + (size_t)n_rows * (guide_w + 2) <= kLdsWords;
 }
-inline size_t saliency_lds_words(int n_rows, int mid_n, size_t fixed_words) {
-  return 2 * (size_t)n_rows + (queue_fits_lds(n_rows, mid_n, fixed_words) ? (size_t)n_rows * (mid_n + 2) : 0);
+inline size_t saliency_lds_words(int n_rows, int guide_w, size_t fixed_words) {
+  return 2 * (size_t)n_rows + (queue_fits_lds(n_rows, guide_w, fixed_words) ? (size_t)n_rows * (guide_w + 2) : 0);
 }
 
 // Eq. 10 for one pair: a candidate's rank is the number of candidates evicted before it
@@ -137,11 +163,11 @@ __device__ void select_survivors(const float* sc, int m, int n_evict, int* src, 
 template <int PPR>  // 16-byte pieces per key row
 __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   extern __shared__ int sm_raw[];
-  const int m = a.mid_n;
-  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
-  int* src = sm_raw + m;                               // [mid_n] source index of survivor slot
-  float* st = reinterpret_cast<float*>(sm_raw + 2 * m);   // [n_rows][2] row statistics
-  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr; // [n_rows][mid_n + 2] queue copy
+  const int m = a.mid_n, w = a.guide_w;
+  float* sc = reinterpret_cast<float*>(sm_raw);        // [guide_w] saliency (mid candidates first)
+  int* src = sm_raw + w;                               // [mid_n] source index of survivor slot
+  float* st = reinterpret_cast<float*>(sm_raw + w + m);   // [n_rows][2] row statistics
+  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr; // [n_rows][guide_w + 2] queue copy
   __shared__ int sm_first;
   __shared__ unsigned long long sm_mask[kMaxWaves];
 
@@ -150,9 +176,10 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const int mid_after = m - a.n_evict;
 
   if (tid == 0) sm_first = m;
-  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
-                 a.score_mode, qs, st, sc);
+  block_saliency(a, a.guide + (size_t)pair * a.line_len * (w + 2), qs, st, sc);
+  if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
+  if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
 
   // Destination rows [first, mid_after + n_tail), relative to mid_lo; rows in front of the
   // first hole stay where they are.
@@ -205,11 +232,12 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
 template <int PPR, int PIECES, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
   extern __shared__ int sm_raw[];
-  const int m = a.mid_n;
-  float* sc = reinterpret_cast<float*>(sm_raw);        // [mid_n] saliency
-  int* dstmap = sm_raw + m;                            // [mid_n] new slot, -1 = evicted
-  float* st = reinterpret_cast<float*>(sm_raw + 2 * m);   // [n_rows][2] row statistics
-  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr; // [n_rows][mid_n + 2] queue copy
+  const int m = a.mid_n, w = a.guide_w;
+  float* sc = reinterpret_cast<float*>(sm_raw);        // [guide_w] saliency (mid candidates first)
+  int* dstmap = sm_raw + w;                            // [mid_n] new slot, -1 = evicted
+  int* src = dstmap + m;                               // [mid_n] source index of survivor slot
+  float* st = reinterpret_cast<float*>(src + m);       // [n_rows][2] row statistics
+  float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr; // [n_rows][guide_w + 2] queue copy
   __shared__ int sm_first;
   __shared__ unsigned long long sm_mask[kMaxWaves];
 
@@ -233,9 +261,10 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
     }
   }
   if (tid == 0) sm_first = m;
-  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
-                 a.score_mode, qs, st, sc);
-  select_survivors(sc, m, a.n_evict, nullptr, dstmap, &sm_first, sm_mask);
+  block_saliency(a, a.guide + (size_t)pair * a.line_len * (w + 2), qs, st, sc);
+  if (a.score_mode == 2) add_accumulated(a, pair, sc);
+  select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
+  if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();   // every row that may move is in registers
 #pragma unroll
@@ -253,17 +282,22 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
   }
 }
 
-// kv_scores: the saliency alone.
-__global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, float* out) {
+// kv_scores: the saliency alone.  With fold != 0 (mode 2 at the end of a line that does not
+// evict) the line's sums are added to the accumulators instead.
+__global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, float* out, int fold) {
   extern __shared__ int sm_raw[];
-  const int m = a.mid_n;
-  float* sc = reinterpret_cast<float*>(sm_raw);
-  float* st = sc + m;
+  float* sc = reinterpret_cast<float*>(sm_raw);        // [guide_w]
+  float* st = sc + a.guide_w;
   float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr;
   const int pair = blockIdx.x;
-  block_saliency(a.guide + (size_t)pair * a.line_len * (m + 2), a.n_rows, a.line_len, m,
-                 a.score_mode, qs, st, sc);
-  for (int j = threadIdx.x; j < m; j += kBlock) out[(size_t)pair * m + j] = sc[j];
+  block_saliency(a, a.guide + (size_t)pair * a.line_len * (a.guide_w + 2), qs, st, sc);
+  if (a.score_mode == 2) add_accumulated(a, pair, sc);
+  if (fold) {
+    float* acc = a.acc + (size_t)pair * a.guide_w;
+    for (int j = threadIdx.x; j < a.n_cols; j += kBlock) acc[j] = sc[j];
+  } else {
+    for (int j = threadIdx.x; j < a.mid_n; j += kBlock) out[(size_t)pair * a.mid_n + j] = sc[j];
+  }
 }
 
 __global__ __launch_bounds__(kBlock) void copy_rows_kernel(uint4* dst, int64_t dst_pitch,
@@ -321,8 +355,9 @@ unsigned grid_for(size_t n) {
 template <int PPR>
 hipError_t launch_evict_t(const EvictArgs& a0, hipStream_t s) {
   EvictArgs a = a0;
-  a.queue_in_lds = queue_fits_lds(a.n_rows, a.mid_n, (size_t)a.mid_n * 2);
-  const size_t dyn = ((size_t)a.mid_n * 2 + saliency_lds_words(a.n_rows, a.mid_n, (size_t)a.mid_n * 2)) * sizeof(int);
+  const size_t fixed = (size_t)a.guide_w + 2 * (size_t)a.mid_n;
+  a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
+  const size_t dyn = (fixed + saliency_lds_words(a.n_rows, a.guide_w, fixed)) * sizeof(int);
   const dim3 grid((unsigned)a.n_pairs);
   const int64_t pieces = (int64_t)(a.mid_n + a.n_tail) * PPR;
   // Measured on the five workloads: with at least two pairs per compute unit the tiled
@@ -350,9 +385,11 @@ hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t
 
 hipError_t launch_saliency(const EvictArgs& a0, float* out, hipStream_t s) {
   EvictArgs a = a0;
-  a.queue_in_lds = queue_fits_lds(a.n_rows, a.mid_n, (size_t)a.mid_n);
-  const size_t dyn = ((size_t)a.mid_n + saliency_lds_words(a.n_rows, a.mid_n, (size_t)a.mid_n)) * sizeof(int);
-  hipLaunchKernelGGL(saliency_kernel, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out);
+  const size_t fixed = (size_t)a.guide_w;
+  a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
+  const size_t dyn = (fixed + saliency_lds_words(a.n_rows, a.guide_w, fixed)) * sizeof(int);
+  hipLaunchKernelGGL(saliency_kernel, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out,
+                     out == nullptr ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -22,7 +22,10 @@ struct DecodeArgs {
   float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
   float* guide;       // [P, n, mid_n + 2] guide queue of the layer, already advanced to this
                       //                   query's row: mid logits (log2 units), then (m, l)
-  int64_t guide_pitch;  // floats between the rows of consecutive pairs = n * (mid_n + 2)
+  int64_t guide_pitch;  // floats between the rows of consecutive pairs = n * (guide_w + 2)
+  int32_t guide_w;    // logits a queue row holds; the row's (m, l) sit behind them
+  int32_t stage_new;  // the appended token's own logit is scored too (accumulated attention)
+  int32_t store_ml;   // the decode softmax's (m, l) are needed (score modes 1 and 2)
   int32_t n_pairs;    // P = Bz * H
   int32_t t;          // keys visible to this query, the new one included
   int32_t t_max;      // row pitch of the caches, in keys
@@ -44,9 +47,15 @@ struct EvictArgs {
   void* kc;
   void* vc;
   int32_t* pos;
-  const float* guide;  // [P, n, mid_n + 2] of the layer
+  const float* guide;  // [P, n, guide_w + 2] of the layer
+  float* acc;          // [P, guide_w] attention accumulated per cache slot behind the anchor (mode 2)
   int32_t n_rows;      // queries queued in the line (n at an end of line)
   int32_t line_len;    // n, the divisor of Eq. 9
+  int32_t guide_w;     // logits per queue row
+  int32_t len0;        // scored keys of the first queued row ...
+  int32_t len_step;    // ... and how many more every later row has (mode 2: 1, else 0)
+  int32_t n_cols;      // columns to sum: mid_n, or every scored key of the line's last row (mode 2)
+  int32_t do_evict;    // 0: only fold the line's queue into acc (mode 2 on lines that do not evict)
   int32_t score_mode;
   int32_t queue_in_lds;  // set by the launcher: the line's queue fits the workgroup's LDS
   int32_t n_pairs;
@@ -62,8 +71,8 @@ int decode_rows_per_group(int dtype, int head_dim);   // keys one wave-wide load
 int decode_max_waves(int depth);                      // wavefronts per workgroup at that depth
 int decode_depth_for(int groups_per_wave);            // smallest instantiated depth >= the argument, 0 if none
 hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s);
-// out[P, mid_n] = saliency of Eq. 9 from the queue rows so far (uses guide, n_rows, line_len,
-// score_mode, n_pairs, mid_n of the arguments).
+// out[P, mid_n] = saliency of the mid candidates from the queue rows so far (Eq. 9; in mode 2
+// the accumulated attention including the rows so far).
 hipError_t launch_saliency(const EvictArgs& a, float* out, hipStream_t s);
 
 // dst[p, 0:rows, :] = src[p, 0:rows, :] for p < n_pairs; pitches in rows; row_bytes % 16 == 0.

@@ -19,6 +19,7 @@ thread_local int g_last_hip_error = 0;
 
 constexpr int kMaxMid = 2048;       // candidates the eviction kernel ranks in LDS
 constexpr int kMaxLine = 4096;      // guide queries whose row statistics it keeps in LDS
+constexpr int kMaxScored = 8192;    // scored slots per pair when attention is accumulated
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -36,16 +37,17 @@ struct Derived {
   int max_split;    // pitch of the split-partial buffers
   float scale;
   // scratch layout (byte offsets)
-  size_t off_guide, off_pos, off_part_o, off_part_ml, total;
-  size_t guide_layer, pos_layer;   // element strides per layer
-  size_t guide_pair;               // floats of one pair's guide queue: n * (mid_n + 2)
+  int guide_w;      // logits per guide-queue row: mid_n, or B - N_init when attention is accumulated
+  size_t off_guide, off_pos, off_acc, off_part_o, off_part_ml, total;
+  size_t guide_layer, pos_layer, acc_layer;   // element strides per layer
+  size_t guide_pair;               // floats of one pair's guide queue: n * (guide_w + 2)
 };
 
 int derive(const linear_cfg_t& c, Derived* d) {
   if (c.n_layers < 1 || c.batch < 1 || c.n_heads < 1) return LINEAR_EINVAL;
   if (c.head_dim != 64 && c.head_dim != 128) return LINEAR_EINVAL;
   if (c.dtype != LINEAR_F32 && c.dtype != LINEAR_BF16) return LINEAR_EINVAL;
-  if (c.score_mode != 0 && c.score_mode != 1) return LINEAR_EINVAL;
+  if (c.score_mode < 0 || c.score_mode > 2) return LINEAR_EINVAL;
   if (c.n_cond < 0 || c.line_len < 1 || c.n_lines < 1) return LINEAR_EINVAL;
   if (!(c.scale >= 0.f) || std::isinf(c.scale)) return LINEAR_EINVAL;
   const int64_t N = (int64_t)c.line_len * c.n_lines;
@@ -69,12 +71,16 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->max_split = linear::kMaxSplit;
   d->scale = c.scale > 0.f ? c.scale : 1.0f / std::sqrt((float)c.head_dim);
   const size_t P = (size_t)d->pairs;
-  d->guide_pair = d->compresses ? (size_t)c.line_len * (d->mid_n + 2) : 0;
+  d->guide_w = !d->compresses ? 0 : (c.score_mode == 2 ? c.budget - c.n_init : d->mid_n);
+  if (d->guide_w > kMaxScored) return LINEAR_EINVAL;
+  d->guide_pair = d->compresses ? (size_t)c.line_len * (d->guide_w + 2) : 0;
   d->guide_layer = P * d->guide_pair;
+  d->acc_layer = c.score_mode == 2 ? P * (size_t)d->guide_w : 0;
   d->pos_layer = P * (size_t)d->t_max;
   size_t off = 0;
   d->off_guide = off;    off = align_up(off + d->guide_layer * c.n_layers * sizeof(float));
   d->off_pos = off;      off = align_up(off + d->pos_layer * c.n_layers * sizeof(int32_t));
+  d->off_acc = off;      off = align_up(off + d->acc_layer * c.n_layers * sizeof(float));
   d->off_part_o = off;   off = align_up(off + P * d->max_split * c.head_dim * sizeof(float));
   d->off_part_ml = off;  off = align_up(off + P * d->max_split * 2 * sizeof(float));
   d->total = off;
@@ -177,6 +183,41 @@ bool line_evicts(const linear_kv& kv, int line /*1-based*/) {
   return kv.d.compresses && line >= kv.d.first_line && line <= kv.cfg.n_lines - 1;
 }
 
+// Arguments of the end-of-line kernels for the layer's current line with `rows` queries queued.
+void fill_line_args(const linear_kv& kv, int layer, int rows, linear::EvictArgs* a) {
+  const linear_cfg_t& c = kv.cfg;
+  const Derived& d = kv.d;
+  const LayerState& ls = kv.layer[layer];
+  *a = linear::EvictArgs{};
+  a->kc = kv.k_cache[layer];
+  a->vc = kv.v_cache[layer];
+  a->pos = reinterpret_cast<int32_t*>(kv.scratch + d.off_pos) + d.pos_layer * layer;
+  a->guide = reinterpret_cast<const float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
+  a->acc = reinterpret_cast<float*>(kv.scratch + d.off_acc) + d.acc_layer * layer;
+  a->n_rows = rows;
+  a->line_len = c.line_len;
+  a->guide_w = d.guide_w;
+  a->score_mode = c.score_mode;
+  a->n_pairs = d.pairs;
+  a->t_max = d.t_max;
+  a->mid_lo = d.mid_lo;
+  a->mid_n = d.mid_n;
+  a->n_evict = c.line_len;
+  a->n_tail = d.n_tail;
+  if (c.score_mode == 2) {
+    // the line's first query saw (keys cached before the line) + 1 keys; every later one sees
+    // one more; the scored ones are those behind the anchor
+    const int t_first = c.n_cond + ls.visual_len - ls.in_line + 1;
+    a->len0 = t_first - d.mid_lo;
+    a->len_step = 1;
+    a->n_cols = std::max(0, std::min(d.guide_w, c.n_cond + ls.visual_len - d.mid_lo));
+  } else {
+    a->len0 = d.mid_n;
+    a->len_step = 0;
+    a->n_cols = d.mid_n;
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -227,7 +268,9 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
-  // Position maps start with the prefix; the guide queues are written before they are read.
+  // Position maps start with the prefix; the guide queues are written before they are read;
+  // attention accumulators start at zero.
+  e = linear::launch_fill_u32(kv->scratch + d.off_acc, 0u, d.acc_layer * cfg->n_layers, s);
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
     int32_t* pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * l;
     e = linear::launch_iota_rows(pos, d.t_max, cfg->n_cond, d.pairs, s);
@@ -276,8 +319,9 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
   a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
   a.guide = reinterpret_cast<float*>(kv->scratch + d.off_guide) + d.guide_layer * layer +
-            (size_t)ls.in_line * (d.mid_n + 2);
+            (size_t)ls.in_line * (d.guide_w + 2);
   a.guide_pitch = (int64_t)d.guide_pair;
+  a.guide_w = d.guide_w;
   a.n_pairs = d.pairs;
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
@@ -291,7 +335,17 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.depth = plan.depth;
   a.max_split = d.max_split;
   a.mid_lo = d.mid_lo;
-  a.mid_n = line_evicts(*kv, line) ? d.mid_n : 0;
+  if (c.score_mode == 2) {
+    // accumulated attention: every key behind the anchor is scored on every line, the
+    // appended one included
+    a.mid_n = d.compresses ? std::max(0, std::min(d.guide_w, a.t - d.mid_lo)) : 0;
+    a.stage_new = 1;
+    a.store_ml = 1;
+  } else {
+    a.mid_n = line_evicts(*kv, line) ? d.mid_n : 0;
+    a.stage_new = 0;
+    a.store_ml = c.score_mode == 1;
+  }
   a.score_mode = c.score_mode;
   a.new_pos = c.n_cond + visual_index;
   a.scale_log2e = d.scale * 1.4426950408889634f;
@@ -310,24 +364,17 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
   const Derived& d = kv->d;
   if (ls.in_line != c.line_len) return LINEAR_ESTATE;
   const int line = ls.lines_done + 1;
-  if (line_evicts(*kv, line)) {
+  const bool evicts = line_evicts(*kv, line);
+  if (evicts || (c.score_mode == 2 && d.compresses)) {
     linear::EvictArgs a;
-    a.kc = kv->k_cache[layer];
-    a.vc = kv->v_cache[layer];
-    a.pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
-    a.guide = reinterpret_cast<const float*>(kv->scratch + d.off_guide) + d.guide_layer * layer;
-    a.n_rows = c.line_len;
-    a.line_len = c.line_len;
-    a.score_mode = c.score_mode;
-    a.n_pairs = d.pairs;
-    a.t_max = d.t_max;
-    a.mid_lo = d.mid_lo;
-    a.mid_n = d.mid_n;
-    a.n_evict = c.line_len;
-    a.n_tail = d.n_tail;
-    const hipError_t e = linear::launch_evict(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
+    fill_line_args(*kv, layer, c.line_len, &a);
+    hipError_t e = hipSuccess;
+    if (evicts)
+      e = linear::launch_evict(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
+    else if (a.n_cols > 0)   // accumulated attention: fold the line's queue into the accumulators
+      e = linear::launch_saliency(a, nullptr, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
-    ls.visual_len -= c.line_len;
+    if (evicts) ls.visual_len -= c.line_len;
   }
   ls.in_line = 0;
   ls.lines_done += 1;
@@ -367,13 +414,8 @@ int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void
   const LayerState& ls = kv->layer[layer];
   if (ls.lines_done >= kv->cfg.n_lines || !line_evicts(*kv, ls.lines_done + 1)) return LINEAR_ESTATE;
   const Derived& d = kv->d;
-  linear::EvictArgs a = {};
-  a.guide = reinterpret_cast<const float*>(kv->scratch + d.off_guide) + d.guide_layer * layer;
-  a.n_rows = ls.in_line;
-  a.line_len = kv->cfg.line_len;
-  a.score_mode = kv->cfg.score_mode;
-  a.n_pairs = d.pairs;
-  a.mid_n = d.mid_n;
+  linear::EvictArgs a;
+  fill_line_args(*kv, layer, ls.in_line, &a);
   const hipError_t e = linear::launch_saliency(a, out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e);
   if (mid_out) *mid_out = d.mid_n;

@@ -32,7 +32,7 @@ def say(msg):
 
 
 @pytest.mark.parametrize("w", [synth.TINY_A, synth.TINY_B, synth.TINY_C], ids=lambda w: w.name)
-@pytest.mark.parametrize("score_mode", [0, 1])
+@pytest.mark.parametrize("score_mode", [0, 1, 2])
 def test_tiny_every_slice(w, score_mode):
     rep = run_parity(w, all_slices(w), score_mode=score_mode)
     say(f"{w.name} mode {score_mode}: {rep}")
@@ -55,6 +55,10 @@ def test_tiny_full_budget_never_evicts():
     (FULL_SPLIT, 16, 1, 0), (FULL_SPLIT, 5, 3, 0), (NO_COND, 0, 0, 0), (NO_COND, 1, 0, 0),
     (F32_D64_LONG, 0, 0, 0), (F32_D64_LONG, 8, 2, 1), (STREAMING, 0, 0, 0), (F32_WIDE, 0, 0, 0),
     (ONE_TOKEN_LINES, 0, 0, 0), (ONE_TOKEN_LINES, 0, 0, 1), (NO_ANCHOR_R3, 0, 0, 0), (NO_ANCHOR_R3, 2, 2, 1),
+    # accumulated attention (score mode 2): scored range grows with the line, crosses splits
+    (MID_SPLIT, 0, 0, 2), (MID_SPLIT, 3, 2, 2), (LUMINA_SLICE, 0, 0, 2), (LUMINA_SLICE, 4, 5, 2),
+    (F32_R2, 0, 0, 2), (NO_COND, 1, 0, 2), (ONE_TOKEN_LINES, 0, 0, 2), (NO_ANCHOR_R3, 0, 0, 2),
+    (F32_WIDE, 0, 0, 2), (STREAMING, 0, 0, 2),
 ], ids=lambda x: getattr(x, "name", str(x)))
 def test_mid_sizes_every_slice(w, gpw, n_split, score_mode):
     rep = run_parity(w, all_slices(w), groups_per_wave=gpw, n_split=n_split, score_mode=score_mode)
@@ -77,6 +81,13 @@ def test_full_size_compressed_sampled_slices(w):
     say(f"{w.name}: {rep}")
     assert rep.steps == w.n_visual
     assert rep.evictions == (w.n_lines - w.budget // w.line_len) * len(_sample(w))
+
+
+def test_full_size_accumulated_attention_sampled_slices():
+    w = synth.LLAMAGEN_XL
+    rep = run_parity(w, _sample(w, n_heads=2), score_mode=2, layers_call=True)
+    say(f"{w.name} mode 2: {rep}")
+    assert rep.steps == w.n_visual and rep.evictions == 20 * len(_sample(w, n_heads=2))
 
 
 @pytest.mark.parametrize("w", [synth.LLAMAGEN_XL, synth.JANUS_PRO_7B], ids=lambda w: w.name)
