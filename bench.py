@@ -223,6 +223,8 @@ def main():
     ap.add_argument("--sequences", type=int, default=0,
                     help="override the number of sequences (e.g. 512 = the paper's Table 4 batch of 256 "
                          "with both guidance halves, for the LlamaGen-XL shape)")
+    ap.add_argument("--budget-lines", type=int, default=0,
+                    help="override the budget B, in raster lines (rho sweeps: 6 of 24 lines = 1/4, ...)")
     ap.add_argument("--score-mode", type=int, default=0,
                     help="0 = Eq. 9 as printed (default), 1 = decode-softmax mass, 2 = accumulated attention")
     ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
@@ -236,9 +238,11 @@ def main():
     from paper_2512_04857_amd import synth
 
     w = synth.WORKLOADS[args.workload]
+    from dataclasses import replace
     if args.sequences:
-        from dataclasses import replace
         w = replace(w, batch=args.sequences, name=f"{w.name}-seq{args.sequences}")
+    if args.budget_lines:
+        w = replace(w, budget=args.budget_lines * w.line_len, name=f"{w.name}-b{args.budget_lines}")
     steps = args.steps or w.n_visual
     if steps > w.n_visual:
         print(f"bench.py: --steps is capped at one image ({w.n_visual} decode steps)", file=sys.stderr)
