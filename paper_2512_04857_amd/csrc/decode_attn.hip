@@ -268,15 +268,21 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     if (lane == 0) sm_m[wave] = m_wave;
   }
   __syncthreads();
-  if (scoring && wave == nw - 1) {
-    // This workgroup's share of the query's guide-queue row (Eq. 8) in one coalesced store,
-    // by the last wavefront while the first one merges; the softmax rows of Eq. 9 are
-    // evaluated once, at the end of the line.  (Issuing it earlier, behind a barrier of its
-    // own between the logits and the V phase, was measured slower.)
-    float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-    const int extra = a.stage_new && split == a.n_split - 1 ? 1 : 0;   // the appended token's entry
-    const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows + extra - a.mid_lo, a.mid_n);
-    for (int j = j0 + lane; j < j1; j += 64) store_nt(&qrow[j], sm_mid[j]);
+  // A query's guide-queue row (Eq. 8) occupies whole, aligned 128-byte lines and a workgroup that
+  // holds all the keys writes all of them, padding included, in one coalesced store: lines
+  // written in part cost a read-modify-write at the memory (measured: 0.3 us per launch).
+  const int extra = a.stage_new && split == a.n_split - 1 ? 1 : 0;   // the appended token's entry
+  const int j0 = max(r0 - a.mid_lo, 0), j1 = min(r0 + n_rows + extra - a.mid_lo, a.mid_n);
+  float* qrow = a.guide + (size_t)pair * a.guide_pitch;
+  if (scoring && wave == nw - 1 && (!a.store_ml || a.n_split > 1)) {
+    // By the last wavefront while the first one merges; the softmax rows of Eq. 9 are evaluated
+    // once, at the end of the line.  (Issuing it earlier, behind a barrier of its own between
+    // the logits and the V phase, was measured slower.)
+    if (a.n_split == 1) {
+      for (int j = lane; j < a.guide_row; j += 64) store_nt(&qrow[j], j < j1 ? sm_mid[j] : 0.f);
+    } else {
+      for (int j = j0 + lane; j < j1; j += 64) store_nt(&qrow[j], sm_mid[j]);
+    }
   }
   if (wave != 0) return;
 
@@ -286,10 +292,12 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     const float inv = 1.0f / l_all;
 #pragma unroll
     for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
-    if (scoring && a.store_ml && lane == 0) {   // the decode softmax's statistics
-      float* qrow = a.guide + (size_t)pair * a.guide_pitch;
-      store_nt(&qrow[a.guide_w], m_all);
-      store_nt(&qrow[a.guide_w + 1], l_all);
+    if (scoring && a.store_ml) {
+      // the row together with the decode softmax's statistics, which only exist now
+      for (int j = lane; j < a.guide_row; j += 64) {
+        const float x = j < j1 ? sm_mid[j] : (j == a.guide_w ? m_all : (j == a.guide_w + 1 ? l_all : 0.f));
+        store_nt(&qrow[j], x);
+      }
     }
     return;
   }

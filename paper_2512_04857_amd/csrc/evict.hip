@@ -29,7 +29,7 @@ __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x)
 //   mode 2 (accumulated attention): sc[j] = sum over the queued queries of the decode-time
 //     probability of scored key j; row r scores len0 + r * len_step keys (the line grows), the
 //     rest of the row is not read.
-// `g` is the pair's queue [n_rows][guide_w + 2] in global memory (logits in log2 units);
+// `g` is the pair's queue [n_rows][guide_row] in global memory (logits in log2 units);
 // `qs_lds` is an LDS copy area of n_rows * (guide_w + 2) floats, or nullptr when the queue is
 // too large for LDS (then the three passes read global memory, where it stays in L2); `st` is
 // LDS space for 2 * n_rows floats.  All threads call it; it ends with a barrier.  Sums run in
@@ -37,11 +37,34 @@ __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x)
 __device__ void block_saliency(const EvictArgs& a, const float* g, float* qs_lds, float* st, float* sc) {
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int n_rows = a.n_rows, mode = a.score_mode;
-  const int pitch = a.guide_w + 2;
-  const int total = n_rows * pitch;
+  int pitch = a.guide_row;            // floats between queue rows where the passes read them
   const float* qs = g;
   if (qs_lds) {
-    for (int i = tid; i < total; i += nthreads) qs_lds[i] = g[i];
+    // the LDS copy drops the padding (and keeps the rows off a common bank)
+    pitch = a.guide_w + 2;
+    // rows are whole 128-byte lines and contiguous: 16-byte loads, four in flight per thread
+    const int row4 = a.guide_row >> 2, total4 = n_rows * row4;
+    const float4* g4 = reinterpret_cast<const float4*>(g);
+    for (int i0 = tid; i0 < total4; i0 += 4 * nthreads) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * nthreads;
+        if (i < total4) v[u] = g4[i];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * nthreads;
+        if (i < total4) {
+          const int r = i / row4, j = (i - r * row4) * 4;
+          float* dst = qs_lds + r * pitch + j;
+          if (j + 0 < pitch) dst[0] = v[u].x;
+          if (j + 1 < pitch) dst[1] = v[u].y;
+          if (j + 2 < pitch) dst[2] = v[u].z;
+          if (j + 3 < pitch) dst[3] = v[u].w;
+        }
+      }
+    }
     qs = qs_lds;
     __syncthreads();
   }
@@ -176,7 +199,7 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const int mid_after = m - a.n_evict;
 
   if (tid == 0) sm_first = m;
-  block_saliency(a, a.guide + (size_t)pair * a.line_len * (w + 2), qs, st, sc);
+  block_saliency(a, a.guide + (size_t)pair * a.line_len * a.guide_row, qs, st, sc);
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
   if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
@@ -261,7 +284,7 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
     }
   }
   if (tid == 0) sm_first = m;
-  block_saliency(a, a.guide + (size_t)pair * a.line_len * (w + 2), qs, st, sc);
+  block_saliency(a, a.guide + (size_t)pair * a.line_len * a.guide_row, qs, st, sc);
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
   if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
@@ -290,7 +313,7 @@ __global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, flo
   float* st = sc + a.guide_w;
   float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr;
   const int pair = blockIdx.x;
-  block_saliency(a, a.guide + (size_t)pair * a.line_len * (a.guide_w + 2), qs, st, sc);
+  block_saliency(a, a.guide + (size_t)pair * a.line_len * a.guide_row, qs, st, sc);
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   if (fold) {
     float* acc = a.acc + (size_t)pair * a.guide_w;

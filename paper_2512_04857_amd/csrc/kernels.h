@@ -20,10 +20,11 @@ struct DecodeArgs {
   float* out;         // [P, d]
   float* part_o;      // [P, max_split, d]   split partial numerators
   float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
-  float* guide;       // [P, n, mid_n + 2] guide queue of the layer, already advanced to this
-                      //                   query's row: mid logits (log2 units), then (m, l)
-  int64_t guide_pitch;  // floats between the rows of consecutive pairs = n * (guide_w + 2)
+  float* guide;       // [P, n, guide_row] guide queue of the layer, already advanced to this
+                      //                   query's row: mid logits (log2 units), then (m, l), then padding
+  int64_t guide_pitch;  // floats between the rows of consecutive pairs = n * guide_row
   int32_t guide_w;    // logits a queue row holds; the row's (m, l) sit behind them
+  int32_t guide_row;  // floats per queue row in memory: guide_w + 2 rounded up to whole 128-byte lines
   int32_t stage_new;  // the appended token's own logit is scored too (accumulated attention)
   int32_t store_ml;   // the decode softmax's (m, l) are needed (score modes 1 and 2)
   int32_t n_pairs;    // P = Bz * H
@@ -47,11 +48,12 @@ struct EvictArgs {
   void* kc;
   void* vc;
   int32_t* pos;
-  const float* guide;  // [P, n, guide_w + 2] of the layer
+  const float* guide;  // [P, n, guide_row] of the layer
   float* acc;          // [P, guide_w] attention accumulated per cache slot behind the anchor (mode 2)
   int32_t n_rows;      // queries queued in the line (n at an end of line)
   int32_t line_len;    // n, the divisor of Eq. 9
   int32_t guide_w;     // logits per queue row
+  int32_t guide_row;   // floats per queue row in memory (whole 128-byte lines)
   int32_t len0;        // scored keys of the first queued row ...
   int32_t len_step;    // ... and how many more every later row has (mode 2: 1, else 0)
   int32_t n_cols;      // columns to sum: mid_n, or every scored key of the line's last row (mode 2)

@@ -40,7 +40,8 @@ struct Derived {
   int guide_w;      // logits per guide-queue row: mid_n, or B - N_init when attention is accumulated
   size_t off_guide, off_pos, off_acc, off_part_o, off_part_ml, total;
   size_t guide_layer, pos_layer, acc_layer;   // element strides per layer
-  size_t guide_pair;               // floats of one pair's guide queue: n * (guide_w + 2)
+  int guide_row;    // floats per queue row in memory: guide_w + 2 rounded up to whole 128-byte lines
+  size_t guide_pair;               // floats of one pair's guide queue: n * guide_row
 };
 
 int derive(const linear_cfg_t& c, Derived* d) {
@@ -73,7 +74,8 @@ int derive(const linear_cfg_t& c, Derived* d) {
   const size_t P = (size_t)d->pairs;
   d->guide_w = !d->compresses ? 0 : (c.score_mode == 2 ? c.budget - c.n_init : d->mid_n);
   if (d->guide_w > kMaxScored) return LINEAR_EINVAL;
-  d->guide_pair = d->compresses ? (size_t)c.line_len * (d->guide_w + 2) : 0;
+  d->guide_row = (d->guide_w + 2 + 31) / 32 * 32;
+  d->guide_pair = d->compresses ? (size_t)c.line_len * d->guide_row : 0;
   d->guide_layer = P * d->guide_pair;
   d->acc_layer = c.score_mode == 2 ? P * (size_t)d->guide_w : 0;
   d->pos_layer = P * (size_t)d->t_max;
@@ -197,6 +199,7 @@ void fill_line_args(const linear_kv& kv, int layer, int rows, linear::EvictArgs*
   a->n_rows = rows;
   a->line_len = c.line_len;
   a->guide_w = d.guide_w;
+  a->guide_row = d.guide_row;
   a->score_mode = c.score_mode;
   a->n_pairs = d.pairs;
   a->t_max = d.t_max;
@@ -319,9 +322,10 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
   a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
   a.guide = reinterpret_cast<float*>(kv->scratch + d.off_guide) + d.guide_layer * layer +
-            (size_t)ls.in_line * (d.guide_w + 2);
+            (size_t)ls.in_line * d.guide_row;
   a.guide_pitch = (int64_t)d.guide_pair;
   a.guide_w = d.guide_w;
+  a.guide_row = d.guide_row;
   a.n_pairs = d.pairs;
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
