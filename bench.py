@@ -95,12 +95,13 @@ class Runner:
         self.stride = self.q[0, 0].numel() * self.q.element_size()
         self.ostride = self.out[0].numel() * 4
 
-    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0, score_mode=0):
+    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0, score_mode=0, guide_queue=0):
         """Times `steps` decode steps of workload variant `wl` (same shapes, its own budget)
         from the start of an image.  Returns a dict of measurements."""
         torch, binding = self.torch, self.binding
         L, n = wl.n_layers, wl.line_len
-        cache = binding.LineARCache(binding.cfg_from_workload(wl, score_mode=score_mode), self.device)
+        cache = binding.LineARCache(binding.cfg_from_workload(wl, score_mode=score_mode, guide_queue=guide_queue),
+                                    self.device)
         lib = binding.lib()
         dsteps, evicts = lib.decode_step_layers, lib.end_of_line_evict_layers
         qb, kb, vb, ob = self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(), self.out.data_ptr()
@@ -196,6 +197,22 @@ class Runner:
         }
 
 
+def cache_memory(w, score_mode, guide_queue=0):
+    """K/V cache and scratch bytes of the compressed and the full-cache handle (Table 4's memory
+    column counts the whole model; this is the cache's share of it)."""
+    from paper_2512_04857_amd import binding
+
+    def sizes(wl, mode, queue):
+        per_layer, scratch = binding.linear_workspace_bytes(
+            binding.cfg_from_workload(wl, score_mode=mode, guide_queue=queue))
+        return 2 * per_layer * wl.n_layers, scratch
+
+    ck, cs = sizes(w, score_mode, guide_queue)
+    fk, fs = sizes(w.full_cache(), 0, 0)
+    return {"compressed_kv_bytes": ck, "compressed_scratch_bytes": cs, "full_kv_bytes": fk,
+            "full_scratch_bytes": fs, "saving": round(1.0 - (ck + cs) / (fk + fs), 4)}
+
+
 def read_traffic(name):
     """HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE,
     scaled by a copy kernel of known size), if a summary for this workload is committed."""
@@ -227,6 +244,8 @@ def main():
                     help="override the budget B, in raster lines (rho sweeps: 6 of 24 lines = 1/4, ...)")
     ap.add_argument("--score-mode", type=int, default=0,
                     help="0 = Eq. 9 as printed (default), 1 = decode-softmax mass, 2 = accumulated attention")
+    ap.add_argument("--guide-queue", type=int, default=0,
+                    help="0: automatic; 1: the guide queue holds logits; 2: it holds the queries (score mode 0 only)")
     ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
     ap.add_argument("--n-split", type=int, default=0, help="decode kernel tuning (0 = automatic)")
     args = ap.parse_args()
@@ -268,7 +287,7 @@ def main():
         log(f"calibration pass (uint8 add kernel): {args.calibrate_copy_mib} MiB read + "
             f"{args.calibrate_copy_mib} MiB written")
         del src, dst
-    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split, args.score_mode)
+    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split, args.score_mode, args.guide_queue)
     log("compressed:", json.dumps(comp))
     full = None if args.skip_full else r.run(w.full_cache(), steps, args.warmup, args.groups_per_wave, args.n_split)
     if full:
@@ -291,7 +310,7 @@ def main():
         "config": {"workload": w.name, "n_layers": w.n_layers, "sequences": w.batch, "n_heads": w.n_heads,
                    "head_dim": w.head_dim, "n_cond": w.n_cond, "grid": f"{w.n_lines}x{w.line_len}",
                    "budget": w.budget, "n_init": w.n_init, "n_recent_lines": w.n_recent_lines,
-                   "score_mode": args.score_mode,
+                   "score_mode": args.score_mode, "guide_queue": args.guide_queue,
                    "launches": "one decode kernel per layer per token, one eviction kernel per layer per line, "
                                "enqueued back to back on one stream (decode_step_layers), no graph"},
         "whole_image_ms": round(comp["total_ms"], 3) if steps == w.n_visual else None,
@@ -313,6 +332,7 @@ def main():
             "launches": comp["decode_launches"],
         },
         "cpu_baseline": cpu,
+        "cache_memory": cache_memory(w, args.score_mode, args.guide_queue),
         "paper_end_to_end_speedup_context": {"value": PAPER_CONTEXT.get(w.name), "hardware": "NVIDIA A800",
                                              "note": "whole-model generation, not this path"},
     }

@@ -49,6 +49,10 @@ extern "C" {
 #define LINEAR_F32 0
 #define LINEAR_BF16 1
 
+#define LINEAR_QUEUE_AUTO 0
+#define LINEAR_QUEUE_LOGITS 1
+#define LINEAR_QUEUE_QUERIES 2
+
 typedef struct linear_kv linear_kv_t; /* opaque; host-side bookkeeping only */
 
 typedef struct {
@@ -71,6 +75,14 @@ typedef struct {
                                 every token behind the anchor carries the sum of the
                                 decode-time probabilities it received from every query since
                                 it was appended, never reset; needs B - N_init <= 8192    */
+  int32_t guide_queue;    /* what the line's guide queue holds (Eq. 8):
+                             LINEAR_QUEUE_QUERIES: the queries themselves, as Eq. 8 prints it;
+                                Eq. 9 is evaluated at the end of the line as the matrix
+                                product Q_guide K_mid^T on the matrix cores.  score_mode 0 only;
+                             LINEAR_QUEUE_LOGITS: every query's logits on the scored keys, taken
+                                from the decode step's own q.k (Eq. 9 then needs no product);
+                             LINEAR_QUEUE_AUTO: queries with score_mode 0 (measured faster on
+                                every benchmark workload), logits otherwise                   */
   float scale;            /* logit scale; 0 selects 1/sqrt(d) (Eq. 2)                 */
 } linear_cfg_t;
 

@@ -209,6 +209,8 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     store_nt(&reinterpret_cast<uint4*>(a.kc)[dst], knr);
     store_nt(&reinterpret_cast<uint4*>(a.vc)[dst], vnr);
     if (seg == 0) store_nt(&a.pos[(size_t)pair * a.t_max + (a.t - 1)], a.new_pos);
+    // Eq. 8 as printed: the query joins the line's guide queue (one aligned row)
+    if (a.qq) store_nt(reinterpret_cast<uint4*>(static_cast<char*>(a.qq) + (size_t)pair * a.qq_pitch) + seg, qr);
   }
   // ---- raw logits q.k and this worker's maximum (Eq. 2; the scale is applied with the shift)
   float s[U];

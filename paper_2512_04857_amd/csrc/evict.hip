@@ -22,6 +22,66 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Eq. 9's product for one pair when the guide queue holds the queries (Eq. 8 as printed):
+// dst[r][j] = (q_r . k_(mid_lo + j)) * scale * log2(e) for the n_rows queued queries and the mid
+// keys, on the matrix cores.  16 x 16 output tiles; a wavefront owns a tile column (16 keys,
+// loaded once) and walks the query tiles MT at a time, all loads of a step issued before its
+// products.  Operand layout of the 16x16 MFMA: lane l supplies row (l % 16) of its operand
+// and the (l / 16)-th quarter of the step's k range -- here 16 bytes of the row, the same
+// quarter for both operands, which is all a dot product needs; the result has column
+// (l % 16) and rows 4 * (l / 16) .. + 3 in lane l.  Rows and columns past the end re-read
+// the last one and are not written.  PPR = 16-byte pieces per row.
+template <int PPR, bool BF16, int MT>
+__device__ void fill_logits(const EvictArgs& a, int pair, float* dst, int dst_pitch) {
+  constexpr int STEPS = PPR / 4;   // 64-byte slices of a row
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n_waves = blockDim.x >> 6;
+  const int r16 = lane & 15, quarter = lane >> 4;
+  const int n_rows = a.n_rows, n_keys = a.mid_n;
+  const int tiles_m = (n_rows + 15) >> 4, tiles_n = (n_keys + 15) >> 4;
+  const uint4* qq = reinterpret_cast<const uint4*>(a.qq) + (size_t)pair * a.line_len * PPR;
+  const uint4* kc = reinterpret_cast<const uint4*>(a.kc) + ((size_t)pair * a.t_max + a.mid_lo) * PPR;
+  for (int tn = wave; tn < tiles_n; tn += n_waves) {
+    const int key = min(tn * 16 + r16, n_keys - 1);
+    uint4 kb[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) kb[s] = kc[(size_t)key * PPR + s * 4 + quarter];
+    for (int tm0 = 0; tm0 < tiles_m; tm0 += MT) {
+      uint4 qa[MT][STEPS];
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        const int row = min((tm0 + t) * 16 + r16, n_rows - 1);
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) qa[t][s] = qq[(size_t)row * PPR + s * 4 + quarter];
+      }
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+          if (BF16) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[t][s]),
+                                                          __builtin_bit_cast(bf16x8, kb[s]), acc, 0, 0, 0);
+          } else {
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[t][s].x), __uint_as_float(kb[s].x), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[t][s].y), __uint_as_float(kb[s].y), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[t][s].z), __uint_as_float(kb[s].z), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[t][s].w), __uint_as_float(kb[s].w), acc, 0, 0, 0);
+          }
+        }
+        const int j = tn * 16 + r16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = (tm0 + t) * 16 + quarter * 4 + i;
+          if (r < n_rows && j < n_keys) dst[(size_t)r * dst_pitch + j] = acc[i] * a.scale_log2e;
+        }
+      }
+    }
+  }
+}
+
 // Column sums of the line's softmax rows for one pair.
 //   modes 0, 1 (Eq. 9): sc[j] = (1/n) sum over the queued queries of their softmax row at mid
 //     key j; mode 0 normalises each row over the mid keys only, mode 1 uses the decode
@@ -32,14 +92,29 @@ __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x)
 // `g` is the pair's queue [n_rows][guide_row] in global memory (logits in log2 units);
 // `qs_lds` is an LDS copy area of n_rows * (guide_w + 2) floats, or nullptr when the queue is
 // too large for LDS (then the three passes read global memory, where it stays in L2); `st` is
-// LDS space for 2 * n_rows floats.  All threads call it; it ends with a barrier.  Sums run in
-// a fixed order, so the result does not depend on timing.
-__device__ void block_saliency(const EvictArgs& a, const float* g, float* qs_lds, float* st, float* sc) {
+// LDS space for 2 * n_rows floats.  With a queue of queries the logits are computed here
+// instead of copied (into `qs_lds`, else into the pair's rows of `a.guide_out`).  All threads
+// call it; it ends with a barrier.  Sums run in a fixed order, so the result does not depend
+// on timing.
+template <int PPR, int MT>
+__device__ void block_saliency(const EvictArgs& a, int pair, float* qs_lds, float* st, float* sc) {
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int n_rows = a.n_rows, mode = a.score_mode;
   int pitch = a.guide_row;            // floats between queue rows where the passes read them
+  const float* g = a.guide + (size_t)pair * a.line_len * a.guide_row;
   const float* qs = g;
-  if (qs_lds) {
+  if (a.qq) {
+    float* dst = qs_lds;
+    if (qs_lds) {
+      pitch = a.guide_w + 2;
+    } else {
+      dst = a.guide_out + (size_t)pair * a.line_len * a.guide_row;
+    }
+    if (a.elem_bf16) fill_logits<PPR, true, MT>(a, pair, dst, pitch);
+    else fill_logits<PPR, false, MT>(a, pair, dst, pitch);
+    qs = dst;
+    __syncthreads();   // also orders the global writes of this workgroup before its reads
+  } else if (qs_lds) {
     // the LDS copy drops the padding (and keeps the rows off a common bank)
     pitch = a.guide_w + 2;
     // rows are whole 128-byte lines and contiguous: 16-byte loads, four in flight per thread
@@ -199,7 +274,7 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const int mid_after = m - a.n_evict;
 
   if (tid == 0) sm_first = m;
-  block_saliency(a, a.guide + (size_t)pair * a.line_len * a.guide_row, qs, st, sc);
+  block_saliency<PPR, 2>(a, pair, qs, st, sc);
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
   if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
@@ -284,7 +359,7 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
     }
   }
   if (tid == 0) sm_first = m;
-  block_saliency(a, a.guide + (size_t)pair * a.line_len * a.guide_row, qs, st, sc);
+  block_saliency<PPR, (PIECES > 4 ? 1 : 2)>(a, pair, qs, st, sc);
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
   if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
@@ -307,13 +382,14 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
 
 // kv_scores: the saliency alone.  With fold != 0 (mode 2 at the end of a line that does not
 // evict) the line's sums are added to the accumulators instead.
+template <int PPR>
 __global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, float* out, int fold) {
   extern __shared__ int sm_raw[];
   float* sc = reinterpret_cast<float*>(sm_raw);        // [guide_w]
   float* st = sc + a.guide_w;
   float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr;
   const int pair = blockIdx.x;
-  block_saliency(a, a.guide + (size_t)pair * a.line_len * a.guide_row, qs, st, sc);
+  block_saliency<PPR, 2>(a, pair, qs, st, sc);
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   if (fold) {
     float* acc = a.acc + (size_t)pair * a.guide_w;
@@ -406,14 +482,25 @@ hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t
   }
 }
 
-hipError_t launch_saliency(const EvictArgs& a0, float* out, hipStream_t s) {
+template <int PPR>
+hipError_t launch_saliency_t(const EvictArgs& a0, float* out, hipStream_t s) {
   EvictArgs a = a0;
   const size_t fixed = (size_t)a.guide_w;
   a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
   const size_t dyn = (fixed + saliency_lds_words(a.n_rows, a.guide_w, fixed)) * sizeof(int);
-  hipLaunchKernelGGL(saliency_kernel, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out,
+  hipLaunchKernelGGL(saliency_kernel<PPR>, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out,
                      out == nullptr ? 1 : 0);
   return hipGetLastError();
+}
+
+hipError_t launch_saliency(const EvictArgs& a, int dtype, int head_dim, float* out, hipStream_t s) {
+  const int row_bytes = head_dim * (dtype == 1 ? 2 : 4);
+  switch (row_bytes / 16) {
+    case 8: return launch_saliency_t<8>(a, out, s);
+    case 16: return launch_saliency_t<16>(a, out, s);
+    case 32: return launch_saliency_t<32>(a, out, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,

@@ -25,6 +25,10 @@ struct DecodeArgs {
   int64_t guide_pitch;  // floats between the rows of consecutive pairs = n * guide_row
   int32_t guide_w;    // logits a queue row holds; the row's (m, l) sit behind them
   int32_t guide_row;  // floats per queue row in memory: guide_w + 2 rounded up to whole 128-byte lines
+  void* qq;           // when not null: the query itself is queued (Eq. 8 as printed) at
+                      //   qq + pair * qq_pitch bytes (the layer's [P, n, d] elem queue, already
+                      //   advanced to this query's row) and mid_n is 0
+  int64_t qq_pitch;   // bytes between consecutive pairs' queues = n * d * sizeof(elem)
   int32_t stage_new;  // the appended token's own logit is scored too (accumulated attention)
   int32_t store_ml;   // the decode softmax's (m, l) are needed (score modes 1 and 2)
   int32_t n_pairs;    // P = Bz * H
@@ -49,6 +53,10 @@ struct EvictArgs {
   void* vc;
   int32_t* pos;
   const float* guide;  // [P, n, guide_row] of the layer
+  float* guide_out;    // query queue only: where the logits go when the queue does not fit LDS
+  const void* qq;      // [P, n, d] elem queue of the line's queries, or null (logits are queued)
+  float scale_log2e;   // logit scale times log2(e) (query queue: applied at the end of the line)
+  int32_t elem_bf16;   // element type of the caches and of the query queue
   float* acc;          // [P, guide_w] attention accumulated per cache slot behind the anchor (mode 2)
   int32_t n_rows;      // queries queued in the line (n at an end of line)
   int32_t line_len;    // n, the divisor of Eq. 9
@@ -75,7 +83,7 @@ int decode_depth_for(int groups_per_wave);            // smallest instantiated d
 hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s);
 // out[P, mid_n] = saliency of the mid candidates from the queue rows so far (Eq. 9; in mode 2
 // the accumulated attention including the rows so far).
-hipError_t launch_saliency(const EvictArgs& a, float* out, hipStream_t s);
+hipError_t launch_saliency(const EvictArgs& a, int dtype, int head_dim, float* out, hipStream_t s);
 
 // dst[p, 0:rows, :] = src[p, 0:rows, :] for p < n_pairs; pitches in rows; row_bytes % 16 == 0.
 hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,

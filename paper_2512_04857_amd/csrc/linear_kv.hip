@@ -38,8 +38,10 @@ struct Derived {
   float scale;
   // scratch layout (byte offsets)
   int guide_w;      // logits per guide-queue row: mid_n, or B - N_init when attention is accumulated
-  size_t off_guide, off_pos, off_acc, off_part_o, off_part_ml, total;
+  bool queries;     // the guide queue holds the queries (Eq. 8 as printed), not their logits
+  size_t off_guide, off_qq, off_pos, off_acc, off_part_o, off_part_ml, total;
   size_t guide_layer, pos_layer, acc_layer;   // element strides per layer
+  size_t qq_layer;                 // bytes of one layer's query queue [P, n, d] elem
   int guide_row;    // floats per queue row in memory: guide_w + 2 rounded up to whole 128-byte lines
   size_t guide_pair;               // floats of one pair's guide queue: n * guide_row
 };
@@ -49,6 +51,8 @@ int derive(const linear_cfg_t& c, Derived* d) {
   if (c.head_dim != 64 && c.head_dim != 128) return LINEAR_EINVAL;
   if (c.dtype != LINEAR_F32 && c.dtype != LINEAR_BF16) return LINEAR_EINVAL;
   if (c.score_mode < 0 || c.score_mode > 2) return LINEAR_EINVAL;
+  if (c.guide_queue < LINEAR_QUEUE_AUTO || c.guide_queue > LINEAR_QUEUE_QUERIES) return LINEAR_EINVAL;
+  if (c.guide_queue == LINEAR_QUEUE_QUERIES && c.score_mode != 0) return LINEAR_EINVAL;   // the other modes score decode-time probabilities
   if (c.n_cond < 0 || c.line_len < 1 || c.n_lines < 1) return LINEAR_EINVAL;
   if (!(c.scale >= 0.f) || std::isinf(c.scale)) return LINEAR_EINVAL;
   const int64_t N = (int64_t)c.line_len * c.n_lines;
@@ -76,11 +80,16 @@ int derive(const linear_cfg_t& c, Derived* d) {
   if (d->guide_w > kMaxScored) return LINEAR_EINVAL;
   d->guide_row = (d->guide_w + 2 + 31) / 32 * 32;
   d->guide_pair = d->compresses ? (size_t)c.line_len * d->guide_row : 0;
-  d->guide_layer = P * d->guide_pair;
+  d->queries = d->compresses && c.score_mode == 0 && c.guide_queue != LINEAR_QUEUE_LOGITS;
+  // With a queue of queries the logits exist only inside the end-of-line kernel (in LDS, or in
+  // one layer's worth of this buffer when they do not fit), so the layers share it.
+  d->guide_layer = d->queries ? 0 : P * d->guide_pair;
+  d->qq_layer = d->queries ? P * (size_t)c.line_len * d->row_bytes : 0;
   d->acc_layer = c.score_mode == 2 ? P * (size_t)d->guide_w : 0;
   d->pos_layer = P * (size_t)d->t_max;
   size_t off = 0;
-  d->off_guide = off;    off = align_up(off + d->guide_layer * c.n_layers * sizeof(float));
+  d->off_guide = off;    off = align_up(off + P * d->guide_pair * (d->queries ? 1 : c.n_layers) * sizeof(float));
+  d->off_qq = off;       off = align_up(off + d->qq_layer * c.n_layers);
   d->off_pos = off;      off = align_up(off + d->pos_layer * c.n_layers * sizeof(int32_t));
   d->off_acc = off;      off = align_up(off + d->acc_layer * c.n_layers * sizeof(float));
   d->off_part_o = off;   off = align_up(off + P * d->max_split * c.head_dim * sizeof(float));
@@ -195,6 +204,10 @@ void fill_line_args(const linear_kv& kv, int layer, int rows, linear::EvictArgs*
   a->vc = kv.v_cache[layer];
   a->pos = reinterpret_cast<int32_t*>(kv.scratch + d.off_pos) + d.pos_layer * layer;
   a->guide = reinterpret_cast<const float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
+  a->guide_out = reinterpret_cast<float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
+  a->qq = d.queries ? kv.scratch + d.off_qq + d.qq_layer * layer : nullptr;
+  a->scale_log2e = d.scale * 1.4426950408889634f;
+  a->elem_bf16 = c.dtype == LINEAR_BF16;
   a->acc = reinterpret_cast<float*>(kv.scratch + d.off_acc) + d.acc_layer * layer;
   a->n_rows = rows;
   a->line_len = c.line_len;
@@ -350,6 +363,12 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
     a.stage_new = 0;
     a.store_ml = c.score_mode == 1;
   }
+  a.qq = nullptr;
+  a.qq_pitch = (int64_t)c.line_len * d.row_bytes;
+  if (d.queries) {
+    if (a.mid_n > 0) a.qq = kv->scratch + d.off_qq + d.qq_layer * layer + (size_t)ls.in_line * d.row_bytes;
+    a.mid_n = 0;   // no logits leave the decode step
+  }
   a.score_mode = c.score_mode;
   a.new_pos = c.n_cond + visual_index;
   a.scale_log2e = d.scale * 1.4426950408889634f;
@@ -376,7 +395,7 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
     if (evicts)
       e = linear::launch_evict(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
     else if (a.n_cols > 0)   // accumulated attention: fold the line's queue into the accumulators
-      e = linear::launch_saliency(a, nullptr, static_cast<hipStream_t>(stream));
+      e = linear::launch_saliency(a, c.dtype, c.head_dim, nullptr, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
     if (evicts) ls.visual_len -= c.line_len;
   }
@@ -420,7 +439,7 @@ int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void
   const Derived& d = kv->d;
   linear::EvictArgs a;
   fill_line_args(*kv, layer, ls.in_line, &a);
-  const hipError_t e = linear::launch_saliency(a, out, static_cast<hipStream_t>(stream));
+  const hipError_t e = linear::launch_saliency(a, kv->cfg.dtype, kv->cfg.head_dim, out, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e);
   if (mid_out) *mid_out = d.mid_n;
   return LINEAR_OK;

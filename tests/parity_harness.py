@@ -65,13 +65,13 @@ class ParityReport:
                 f"sanctioned={self.sanctioned} min_gap={self.min_gap:.3e}")
 
 
-def run_parity(w, slices, *, device="cuda:0", score_mode=0, groups_per_wave=0, n_split=0, steps=None,
+def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, groups_per_wave=0, n_split=0, steps=None,
                seed=synth.BASE_SEED, check_scores=True, progress=None, layers_call=False) -> ParityReport:
     """Runs workload `w` on the GPU at its full shape and the oracle on `slices`
     ((layer, sequence, head) triples).  Raises AssertionError on disagreement."""
     o = oracle()
     rep = ParityReport()
-    cfg = binding.cfg_from_workload(w, score_mode=score_mode)
+    cfg = binding.cfg_from_workload(w, score_mode=score_mode, guide_queue=guide_queue)
     cache = binding.LineARCache(cfg, device)
     kc, vc = synth.cond_kv(w, device, seed)
     cache.start_image(kc, vc)

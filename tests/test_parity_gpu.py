@@ -66,6 +66,24 @@ def test_mid_sizes_every_slice(w, gpw, n_split, score_mode):
     assert rep.steps == w.n_visual
 
 
+# Score mode 0 queues the queries by default (Eq. 8 as printed; Eq. 9 is then a matrix product
+# at the end of the line, the oracle's own formulation), so the tests above cover that path:
+# bf16 and fp32 operands, both head sizes, one and several workgroups per pair, query tiles that
+# are full, ragged and single-row, mid regions that are not a multiple of the 16-key tile.
+# These run mode 0 with the other queue, the decode step's own logits.
+@pytest.mark.parametrize("w,gpw,n_split", [
+    (synth.TINY_A, 0, 0), (synth.TINY_B, 0, 0), (synth.TINY_C, 0, 0),
+    (MID_SPLIT, 0, 0), (MID_SPLIT, 3, 2), (LUMINA_SLICE, 0, 0), (LUMINA_SLICE, 4, 5), (F32_R2, 0, 0),
+    (F32_R2, 2, 2), (NO_COND, 1, 0), (F32_D64_LONG, 0, 0), (STREAMING, 0, 0), (F32_WIDE, 0, 0),
+    (ONE_TOKEN_LINES, 0, 0), (NO_ANCHOR_R3, 0, 0),
+], ids=lambda x: getattr(x, "name", str(x)))
+def test_logits_queue_every_slice(w, gpw, n_split):
+    rep = run_parity(w, all_slices(w), groups_per_wave=gpw, n_split=n_split,
+                     guide_queue=binding.LINEAR_QUEUE_LOGITS)
+    say(f"{w.name} logits queue, groups/wave {gpw} splits {n_split}: {rep}")
+    assert rep.steps == w.n_visual
+
+
 def _sample(w, n_heads=4):
     heads = sorted({0, w.n_heads // 3, w.n_heads // 2, w.n_heads - 1})[:n_heads]
     return sampled_slices(w, sorted({0, w.n_layers - 1}), sorted({0, w.batch - 1}), heads)
@@ -81,6 +99,15 @@ def test_full_size_compressed_sampled_slices(w):
     say(f"{w.name}: {rep}")
     assert rep.steps == w.n_visual
     assert rep.evictions == (w.n_lines - w.budget // w.line_len) * len(_sample(w))
+
+
+@pytest.mark.parametrize("w", [synth.LLAMAGEN_XL, synth.JANUS_PRO_7B, synth.LUMINA_768], ids=lambda w: w.name)
+def test_full_size_logits_queue_sampled_slices(w):
+    rep = run_parity(w, _sample(w, n_heads=2), guide_queue=binding.LINEAR_QUEUE_LOGITS,
+                     progress=say if w.n_lines > 30 else None, layers_call=True)
+    say(f"{w.name} logits queue: {rep}")
+    assert rep.steps == w.n_visual
+    assert rep.evictions == (w.n_lines - w.budget // w.line_len) * len(_sample(w, n_heads=2))
 
 
 def test_full_size_accumulated_attention_sampled_slices():
@@ -176,7 +203,8 @@ def test_repeatable_bit_for_bit():
         assert torch.equal(a, b)
 
 
-def test_scores_in_mid_line_and_gather_options():
+@pytest.mark.parametrize("guide_queue", [binding.LINEAR_QUEUE_LOGITS, binding.LINEAR_QUEUE_QUERIES], ids=["logits", "queries"])
+def test_scores_in_mid_line_and_gather_options(guide_queue):
     """kv_scores before the line is complete returns the partial sum of Eq. 9 over the queries
     queued so far (still divided by n); kv_gather accepts NULL outputs."""
     import numpy as np
@@ -185,7 +213,7 @@ def test_scores_in_mid_line_and_gather_options():
     o = oracle()
     w = synth.shrink(synth.TINY_C, n_heads=2)
     dev = "cuda:0"
-    cache = binding.LineARCache(binding.cfg_from_workload(w))
+    cache = binding.LineARCache(binding.cfg_from_workload(w, guide_queue=guide_queue))
     kc, vc = synth.cond_kv(w, dev)
     cache.start_image(kc, vc)
     out = torch.empty((w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
@@ -278,14 +306,15 @@ def test_layers_entry_points_report_errors():
     cache.close()
 
 
+@pytest.mark.parametrize("guide_queue", [binding.LINEAR_QUEUE_LOGITS, binding.LINEAR_QUEUE_QUERIES], ids=["logits", "queries"])
 @pytest.mark.parametrize("budget,lines", [(1608, 203), (1672, 211)], ids=["queue-in-lds", "queue-in-l2"])
-def test_largest_mid_regions(budget, lines):
+def test_largest_mid_regions(budget, lines, guide_queue):
     """Mid regions of 1600 candidates (at n = 8 the largest whose guide queue the end-of-line
     kernel still copies to LDS) and of 1664 (read from global memory instead), with the keys
     split over two workgroups: two evictions each, oracle on both heads."""
     w = synth.Workload("largest-mid", 1, 1, 2, 64, 5, 8, lines, budget, 0, 1, "bf16", 33)
-    rep = run_parity(w, all_slices(w), progress=None)
-    say(f"{w.name} B={budget}: {rep}")
+    rep = run_parity(w, all_slices(w), progress=None, guide_queue=guide_queue)
+    say(f"{w.name} B={budget} queue {guide_queue}: {rep}")
     assert rep.evictions == 2 * 2 and rep.steps == w.n_visual
     with pytest.raises(binding.LinearError):      # more than 2048 candidates are refused
         binding.linear_workspace_bytes(binding.cfg_from_workload(
