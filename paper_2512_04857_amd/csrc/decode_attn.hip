@@ -14,7 +14,8 @@
 //   * every group of LPR lanes is an independent softmax worker over its own rows (max and
 //     sum stay in-lane); workers meet once, in LDS, where the first wavefront merges them;
 //   * the new token is one extra row taken from the inputs; one wavefront counts it and
-//     writes it to the cache (Eq. 4);
+//     writes it to the cache (Eq. 4); its original position is implied by its row (only the
+//     survivors of evictions need a position map, and the end-of-line kernel keeps it);
 //   * on lines that end in an eviction the logits of the mid keys are appended to the line's
 //     guide queue (Eq. 8), staged through LDS so that they leave as one coalesced store; the
 //     softmax rows of Eq. 9 are evaluated once per line by the eviction kernel, so a decode
@@ -36,7 +37,6 @@ __device__ __forceinline__ float ninf() { return -__builtin_inff(); }
 // Results are written once and read by a later kernel: nontemporal stores keep them from
 // sitting dirty in L2 until the end-of-kernel write-back.
 __device__ __forceinline__ void store_nt(float* p, float v) { __builtin_nontemporal_store(v, p); }
-__device__ __forceinline__ void store_nt(int32_t* p, int32_t v) { __builtin_nontemporal_store(v, p); }
 __device__ __forceinline__ void store_nt(uint4* p, const uint4& v) {
   __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(p));
 }
@@ -208,7 +208,6 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     const size_t dst = ((size_t)pair * a.t_max + (a.t - 1)) * LPR + seg;
     store_nt(&reinterpret_cast<uint4*>(a.kc)[dst], knr);
     store_nt(&reinterpret_cast<uint4*>(a.vc)[dst], vnr);
-    if (seg == 0) store_nt(&a.pos[(size_t)pair * a.t_max + (a.t - 1)], a.new_pos);
     // Eq. 8 as printed: the query joins the line's guide queue (one aligned row)
     if (a.qq) store_nt(reinterpret_cast<uint4*>(static_cast<char*>(a.qq) + (size_t)pair * a.qq_pitch) + seg, qr);
   }

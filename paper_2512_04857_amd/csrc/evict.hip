@@ -204,6 +204,38 @@ __device__ void compact_accumulated(const EvictArgs& a, int pair, const float* s
     acc[d] = d < mid_after ? sc[src[d]] : (d < moved ? sc[d + a.n_evict] : 0.f);
 }
 
+// Original positions of the survivors: slot d of the compacted mid region holds candidate
+// src[d], whose position is in the map if it survived an earlier eviction and follows from its
+// index otherwise (the candidates behind the mapped ones are one whole line of consecutive
+// tokens).  Every entry must be read before any is written: the caller puts a barrier (the one
+// its row moves need anyway) between the two calls.
+template <int BLOCK>
+struct SurvivorPositions {
+  static constexpr int PER = (kMaxMid + BLOCK - 1) / BLOCK;
+  int32_t pv[PER];
+  __device__ __forceinline__ void load(const EvictArgs& a, int pair, const int* src) {
+    const int32_t* map = a.pos + (size_t)pair * a.pos_pitch;
+    const int mid_after = a.mid_n - a.n_evict;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int d = i * BLOCK + (int)threadIdx.x;
+      if (d < mid_after) {
+        const int s = src[d];
+        pv[i] = s < a.pos_mapped ? map[s] : a.pos_base + s - a.pos_mapped;
+      }
+    }
+  }
+  __device__ __forceinline__ void store(const EvictArgs& a, int pair) const {
+    int32_t* map = a.pos + (size_t)pair * a.pos_pitch;
+    const int mid_after = a.mid_n - a.n_evict;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int d = i * BLOCK + (int)threadIdx.x;
+      if (d < mid_after) map[d] = pv[i];
+    }
+  }
+};
+
 // LDS words block_saliency needs beyond sc[]: the row statistics, and the queue copy when the
 // whole allocation stays within the 64 KiB every workgroup may use (`fixed_words` = what the
 // calling kernel keeps besides).
@@ -278,6 +310,8 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
   if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
+  SurvivorPositions<kBlock> sp;
+  sp.load(a, pair, src);   // its latency overlaps with the first tile's loads
 
   // Destination rows [first, mid_after + n_tail), relative to mid_lo; rows in front of the
   // first hole stay where they are.
@@ -286,13 +320,11 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const size_t row_base = (size_t)pair * a.t_max + a.mid_lo;
   uint4* kc = reinterpret_cast<uint4*>(a.kc) + row_base * PPR;
   uint4* vc = reinterpret_cast<uint4*>(a.vc) + row_base * PPR;
-  int32_t* pos = a.pos + row_base;
 
   constexpr int kTile = kBlock * kPiecesPerThread;
   const int n_pieces = n_move * PPR;
   for (int t0 = 0; t0 < n_pieces; t0 += kTile) {
     uint4 kr[kPiecesPerThread], vr[kPiecesPerThread];
-    int32_t pr[kPiecesPerThread];
 #pragma unroll
     for (int i = 0; i < kPiecesPerThread; ++i) {
       const int piece = t0 + i * kBlock + tid;
@@ -301,11 +333,11 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
         const int s = d < mid_after ? src[d] : d + a.n_evict;
         kr[i] = kc[(size_t)s * PPR + c];
         vr[i] = vc[(size_t)s * PPR + c];
-        if (c == 0) pr[i] = pos[s];
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // every source row of the tile is in registers
+    if (t0 == 0) sp.store(a, pair);
 #pragma unroll
     for (int i = 0; i < kPiecesPerThread; ++i) {
       const int piece = t0 + i * kBlock + tid;
@@ -315,7 +347,6 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
         // compaction's store phase takes 4 us instead of 10 at 1280 pairs).
         __builtin_nontemporal_store(__builtin_bit_cast(u32x4, kr[i]), reinterpret_cast<u32x4*>(&kc[(size_t)d * PPR + c]));
         __builtin_nontemporal_store(__builtin_bit_cast(u32x4, vr[i]), reinterpret_cast<u32x4*>(&vc[(size_t)d * PPR + c]));
-        if (c == 0) __builtin_nontemporal_store(pr[i], &pos[d]);
       }
     }
   }
@@ -344,18 +375,15 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
   const size_t row_base = (size_t)pair * a.t_max + a.mid_lo;
   uint4* kc = reinterpret_cast<uint4*>(a.kc) + row_base * PPR;
   uint4* vc = reinterpret_cast<uint4*>(a.vc) + row_base * PPR;
-  int32_t* pos = a.pos + row_base;
   const int n_pieces = (m + a.n_tail) * PPR;           // host: <= BLOCK * PIECES
 
   uint4 kr[PIECES], vr[PIECES];
-  int32_t pr[PIECES];
 #pragma unroll
   for (int i = 0; i < PIECES; ++i) {
     const int piece = i * BLOCK + tid;                 // rows are contiguous: piece = 16-byte index
     if (piece < n_pieces) {
       kr[i] = kc[piece];
       vr[i] = vc[piece];
-      if (piece % PPR == 0) pr[i] = pos[piece / PPR];
     }
   }
   if (tid == 0) sm_first = m;
@@ -363,8 +391,11 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
   if (a.score_mode == 2) add_accumulated(a, pair, sc);
   select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
   if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
+  SurvivorPositions<BLOCK> sp;
+  sp.load(a, pair, src);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();   // every row that may move is in registers
+  __syncthreads();   // every row that may move, and every mapped position, is in registers
+  sp.store(a, pair);
 #pragma unroll
   for (int i = 0; i < PIECES; ++i) {
     const int piece = i * BLOCK + tid;
@@ -374,7 +405,6 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
       if (d >= 0 && d != s) {
         __builtin_nontemporal_store(__builtin_bit_cast(u32x4, kr[i]), reinterpret_cast<u32x4*>(&kc[(size_t)d * PPR + c]));
         __builtin_nontemporal_store(__builtin_bit_cast(u32x4, vr[i]), reinterpret_cast<u32x4*>(&vc[(size_t)d * PPR + c]));
-        if (c == 0) __builtin_nontemporal_store(pr[i], &pos[d]);
       }
     }
   }
@@ -418,22 +448,17 @@ __global__ __launch_bounds__(kBlock) void zero_rows_kernel(uint4* dst, int64_t d
   }
 }
 
-__global__ __launch_bounds__(kBlock) void iota_rows_kernel(int32_t* pos, int64_t pitch, int32_t rows,
-                                                           int64_t total) {
+__global__ __launch_bounds__(kBlock) void positions_kernel(int32_t* out, const int32_t* map, int32_t map_pitch,
+                                                           int32_t mid_lo, int32_t mapped, int32_t len,
+                                                           int32_t newest, int64_t total) {
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
        i += (int64_t)gridDim.x * kBlock) {
-    const int64_t p = i / rows, r = i % rows;
-    pos[p * pitch + r] = (int32_t)r;
-  }
-}
-
-__global__ __launch_bounds__(kBlock) void copy_i32_rows_kernel(int32_t* dst, int64_t dst_pitch,
-                                                               const int32_t* src, int64_t src_pitch,
-                                                               int32_t rows, int64_t total) {
-  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
-       i += (int64_t)gridDim.x * kBlock) {
-    const int64_t p = i / rows, r = i % rows;
-    dst[p * dst_pitch + r] = src[p * src_pitch + r];
+    const int64_t p = i / len;
+    const int32_t j = (int32_t)(i % len);
+    int32_t v = j;
+    if (j >= mid_lo + mapped) v = newest - (len - 1 - j);
+    else if (j >= mid_lo) v = map[p * map_pitch + (j - mid_lo)];
+    out[i] = v;
   }
 }
 
@@ -525,21 +550,12 @@ hipError_t launch_zero_rows(void* dst, int64_t dst_pitch_rows, int32_t rows, int
   return hipGetLastError();
 }
 
-hipError_t launch_iota_rows(int32_t* pos, int64_t pitch, int32_t rows, int32_t n_pairs,
-                            hipStream_t s) {
-  if (rows <= 0 || n_pairs <= 0) return hipSuccess;
-  const int64_t total = (int64_t)rows * n_pairs;
-  hipLaunchKernelGGL(iota_rows_kernel, dim3(grid_for((size_t)total)), dim3(kBlock), 0, s, pos, pitch,
-                     rows, total);
-  return hipGetLastError();
-}
-
-hipError_t launch_copy_i32_rows(int32_t* dst, int64_t dst_pitch, const int32_t* src,
-                                int64_t src_pitch, int32_t rows, int32_t n_pairs, hipStream_t s) {
-  if (rows <= 0 || n_pairs <= 0) return hipSuccess;
-  const int64_t total = (int64_t)rows * n_pairs;
-  hipLaunchKernelGGL(copy_i32_rows_kernel, dim3(grid_for((size_t)total)), dim3(kBlock), 0, s, dst,
-                     dst_pitch, src, src_pitch, rows, total);
+hipError_t launch_positions(int32_t* out, const int32_t* map, int32_t map_pitch, int32_t mid_lo,
+                            int32_t mapped, int32_t len, int32_t newest, int32_t n_pairs, hipStream_t s) {
+  if (len <= 0 || n_pairs <= 0) return hipSuccess;
+  const int64_t total = (int64_t)len * n_pairs;
+  hipLaunchKernelGGL(positions_kernel, dim3(grid_for((size_t)total)), dim3(kBlock), 0, s, out, map,
+                     map_pitch, mid_lo, mapped, len, newest, total);
   return hipGetLastError();
 }
 

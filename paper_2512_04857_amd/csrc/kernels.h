@@ -8,6 +8,7 @@ namespace linear {
 
 constexpr int kBlock = 256;        // workgroup size of the eviction and copy kernels
 constexpr int kMaxSplit = 64;      // workgroups one pair's keys may be split over
+constexpr int kMaxMid = 2048;      // mid candidates the end-of-line kernels rank and map
 
 // One decode step of one layer (Eq. 2-4 plus the per-query term of Eq. 9).
 struct DecodeArgs {
@@ -16,7 +17,6 @@ struct DecodeArgs {
   const void* v_new;  // [P, d] elem
   void* kc;           // [P, t_max, d] elem
   void* vc;           // [P, t_max, d] elem
-  int32_t* pos;       // [P, t_max]
   float* out;         // [P, d]
   float* part_o;      // [P, max_split, d]   split partial numerators
   float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
@@ -43,7 +43,6 @@ struct DecodeArgs {
   int32_t mid_lo;     // first mid key (cache row index)
   int32_t mid_n;      // mid keys to score at this step (0: none)
   int32_t score_mode;
-  int32_t new_pos;    // original position of the appended token
   float scale_log2e;  // logit scale times log2(e)
 };
 
@@ -51,7 +50,10 @@ struct DecodeArgs {
 struct EvictArgs {
   void* kc;
   void* vc;
-  int32_t* pos;
+  int32_t* pos;        // [P, pos_pitch] original positions of the mid survivors (see pos_mapped)
+  int32_t pos_pitch;
+  int32_t pos_mapped;  // mid candidates 0 .. pos_mapped-1 have their position in the map; the
+  int32_t pos_base;    //   others are consecutive tokens: candidate j sits at pos_base + j - pos_mapped
   const float* guide;  // [P, n, guide_row] of the layer
   float* guide_out;    // query queue only: where the logits go when the queue does not fit LDS
   const void* qq;      // [P, n, d] elem queue of the line's queries, or null (logits are queued)
@@ -92,12 +94,10 @@ hipError_t launch_copy_rows(void* dst, int64_t dst_pitch_rows, const void* src,
 // dst[p, 0:rows, :] = 0.
 hipError_t launch_zero_rows(void* dst, int64_t dst_pitch_rows, int32_t rows, int32_t n_pairs,
                             int32_t row_bytes, hipStream_t s);
-// pos[p, j] = j for j < rows.
-hipError_t launch_iota_rows(int32_t* pos, int64_t pitch, int32_t rows, int32_t n_pairs,
-                            hipStream_t s);
-// dst[p, 0:rows] = src[p, 0:rows] (int32), pitches in elements.
-hipError_t launch_copy_i32_rows(int32_t* dst, int64_t dst_pitch, const int32_t* src,
-                                int64_t src_pitch, int32_t rows, int32_t n_pairs, hipStream_t s);
+// out[p, j] for j < len = original position of cache row j: j in front of mid_lo, the map's
+// entry for the `mapped` rows from mid_lo on, and consecutive positions ending at `newest` behind.
+hipError_t launch_positions(int32_t* out, const int32_t* map, int32_t map_pitch, int32_t mid_lo,
+                            int32_t mapped, int32_t len, int32_t newest, int32_t n_pairs, hipStream_t s);
 hipError_t launch_fill_u32(void* dst, uint32_t value, size_t n_words, hipStream_t s);
 
 }  // namespace linear

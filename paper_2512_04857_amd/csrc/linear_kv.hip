@@ -17,7 +17,7 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-constexpr int kMaxMid = 2048;       // candidates the eviction kernel ranks in LDS
+using linear::kMaxMid;              // candidates the eviction kernel ranks in LDS
 constexpr int kMaxLine = 4096;      // guide queries whose row statistics it keeps in LDS
 constexpr int kMaxScored = 8192;    // scored slots per pair when attention is accumulated
 constexpr size_t kAlign = 256;
@@ -42,6 +42,7 @@ struct Derived {
   size_t off_guide, off_qq, off_pos, off_acc, off_part_o, off_part_ml, total;
   size_t guide_layer, pos_layer, acc_layer;   // element strides per layer
   size_t qq_layer;                 // bytes of one layer's query queue [P, n, d] elem
+  int pos_pitch;                   // entries per pair of the survivor position map
   int guide_row;    // floats per queue row in memory: guide_w + 2 rounded up to whole 128-byte lines
   size_t guide_pair;               // floats of one pair's guide queue: n * guide_row
 };
@@ -86,7 +87,11 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->guide_layer = d->queries ? 0 : P * d->guide_pair;
   d->qq_layer = d->queries ? P * (size_t)c.line_len * d->row_bytes : 0;
   d->acc_layer = c.score_mode == 2 ? P * (size_t)d->guide_w : 0;
-  d->pos_layer = P * (size_t)d->t_max;
+  // Original positions are kept only for the survivors of evictions, mid_n - n per pair: every
+  // other row's position follows from its index (prefix and anchor in front, whole consecutive
+  // lines behind).
+  d->pos_pitch = d->compresses ? std::max(1, d->mid_n - c.line_len) : 1;
+  d->pos_layer = P * (size_t)d->pos_pitch;
   size_t off = 0;
   d->off_guide = off;    off = align_up(off + P * d->guide_pair * (d->queries ? 1 : c.n_layers) * sizeof(float));
   d->off_qq = off;       off = align_up(off + d->qq_layer * c.n_layers);
@@ -109,6 +114,7 @@ struct LayerState {
   int visual_len = 0;      // visual tokens cached
   int in_line = 0;         // decode steps since the last end of line
   int lines_done = 0;
+  int mapped = 0;          // mid rows whose original position is in the survivor map
 };
 
 }  // namespace
@@ -203,6 +209,12 @@ void fill_line_args(const linear_kv& kv, int layer, int rows, linear::EvictArgs*
   a->kc = kv.k_cache[layer];
   a->vc = kv.v_cache[layer];
   a->pos = reinterpret_cast<int32_t*>(kv.scratch + d.off_pos) + d.pos_layer * layer;
+  a->pos_pitch = d.pos_pitch;
+  a->pos_mapped = ls.mapped;
+  // candidates behind the mapped ones: before the first eviction every mid row still sits at
+  // its own index; afterwards they are the line that has just left the recent window
+  a->pos_base = ls.mapped == 0 ? d.mid_lo
+                               : c.n_cond + (ls.lines_done - c.n_recent_lines) * c.line_len;
   a->guide = reinterpret_cast<const float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
   a->guide_out = reinterpret_cast<float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
   a->qq = d.queries ? kv.scratch + d.off_qq + d.qq_layer * layer : nullptr;
@@ -284,12 +296,10 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
-  // Position maps start with the prefix; the guide queues are written before they are read;
+  // The guide queues and the survivor position maps are written before they are read;
   // attention accumulators start at zero.
   e = linear::launch_fill_u32(kv->scratch + d.off_acc, 0u, d.acc_layer * cfg->n_layers, s);
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
-    int32_t* pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * l;
-    e = linear::launch_iota_rows(pos, d.t_max, cfg->n_cond, d.pairs, s);
     if (e == hipSuccess && cfg->n_cond == 0) {
       // With an empty cache the first step's masked loads touch row 0: give it defined bits.
       e = linear::launch_zero_rows(kv->k_cache[l], d.t_max, 1, d.pairs, d.row_bytes, s);
@@ -323,14 +333,12 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   if (ls.visual_len >= c.budget) return LINEAR_ESTATE;       // cannot happen in a valid sequence
 
   const int line = ls.lines_done + 1;
-  const int visual_index = ls.lines_done * c.line_len + ls.in_line;   // 0-based token i-1
   linear::DecodeArgs a;
   a.q = q;
   a.k_new = k;
   a.v_new = v;
   a.kc = kv->k_cache[layer];
   a.vc = kv->v_cache[layer];
-  a.pos = reinterpret_cast<int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
   a.out = static_cast<float*>(out);
   a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
   a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
@@ -370,7 +378,6 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
     a.mid_n = 0;   // no logits leave the decode step
   }
   a.score_mode = c.score_mode;
-  a.new_pos = c.n_cond + visual_index;
   a.scale_log2e = d.scale * 1.4426950408889634f;
   const hipError_t e = linear::launch_decode(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e);
@@ -397,7 +404,10 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
     else if (a.n_cols > 0)   // accumulated attention: fold the line's queue into the accumulators
       e = linear::launch_saliency(a, c.dtype, c.head_dim, nullptr, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
-    if (evicts) ls.visual_len -= c.line_len;
+    if (evicts) {
+      ls.visual_len -= c.line_len;
+      ls.mapped = d.mid_n - c.line_len;
+    }
   }
   ls.in_line = 0;
   ls.lines_done += 1;
@@ -461,8 +471,10 @@ int kv_gather(linear_kv_t* kv, int32_t layer, void* k_out, void* v_out, int32_t*
   if (e == hipSuccess && v_out)
     e = linear::launch_copy_rows(v_out, len, kv->v_cache[layer], d.t_max, len, d.pairs, d.row_bytes, s);
   if (e == hipSuccess && pos_out) {
-    const int32_t* pos = reinterpret_cast<const int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
-    e = linear::launch_copy_i32_rows(pos_out, len, pos, d.t_max, len, d.pairs, s);
+    const LayerState& ls = kv->layer[layer];
+    const int32_t* map = reinterpret_cast<const int32_t*>(kv->scratch + d.off_pos) + d.pos_layer * layer;
+    const int newest = kv->cfg.n_cond + ls.lines_done * kv->cfg.line_len + ls.in_line - 1;
+    e = linear::launch_positions(pos_out, map, d.pos_pitch, d.mid_lo, ls.mapped, len, newest, d.pairs, s);
   }
   if (e != hipSuccess) return hip_fail(e);
   if (len_out) *len_out = len;
