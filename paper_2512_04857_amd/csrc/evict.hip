@@ -239,12 +239,32 @@ struct SurvivorPositions {
 // LDS words block_saliency needs beyond sc[]: the row statistics, and the queue copy when the
 // whole allocation stays within the 64 KiB every workgroup may use (`fixed_words` = what the
 // calling kernel keeps besides).
-constexpr size_t kLdsWords = (64 * 1024 - 256) / 4;
+// LDS a workgroup of the end-of-line kernels may allocate dynamically, in words: what the
+// device reports (64 KiB on older parts, 160 KiB here), less the kernels' static arrays.
+size_t lds_limit_words() {
+  static const size_t words = [] {
+    int dev = 0, bytes = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+      bytes = 0;
+    if (bytes < 64 * 1024) bytes = 64 * 1024;
+    if (bytes > 160 * 1024) bytes = 160 * 1024;
+    return (size_t)(bytes - 256) / 4;
+  }();
+  return words;
+}
 inline bool queue_fits_lds(int n_rows, int guide_w, size_t fixed_words) {
-  return fixed_words + 2 * (size_t)n_rows + (size_t)n_rows * (guide_w + 2) <= kLdsWords;
+  return fixed_words + 2 * (size_t)n_rows + (size_t)n_rows * (guide_w + 2) <= lds_limit_words();
 }
 inline size_t saliency_lds_words(int n_rows, int guide_w, size_t fixed_words) {
   return 2 * (size_t)n_rows + (queue_fits_lds(n_rows, guide_w, fixed_words) ? (size_t)n_rows * (guide_w + 2) : 0);
+}
+// A kernel that asks for more than the 64 KiB every device grants must be told so first.
+template <class K>
+hipError_t allow_lds(K kernel, size_t dyn_bytes) {
+  if (dyn_bytes <= 64 * 1024 - 256) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)dyn_bytes);
 }
 
 // Eq. 10 for one pair: a candidate's rank is the number of candidates evicted before it
@@ -488,12 +508,17 @@ hipError_t launch_evict_t(const EvictArgs& a0, hipStream_t s) {
   // kernel wins (it never reads the evicted rows); with fewer pairs than that and more than
   // one tile of rows (Lumina: 256 pairs, 245 rows of 256 B) the register-resident kernel with
   // 16 wavefronts per pair is 1.5x faster.
-  if (a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4)
+  hipError_t e;
+  if (a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4) {
+    if ((e = allow_lds(evict_fast_kernel<PPR, 4, 1024>, dyn)) != hipSuccess) return e;
     hipLaunchKernelGGL((evict_fast_kernel<PPR, 4, 1024>), grid, dim3(1024), dyn, s, a);
-  else if (a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8)
+  } else if (a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8) {
+    if ((e = allow_lds(evict_fast_kernel<PPR, 8, 1024>, dyn)) != hipSuccess) return e;
     hipLaunchKernelGGL((evict_fast_kernel<PPR, 8, 1024>), grid, dim3(1024), dyn, s, a);
-  else
+  } else {
+    if ((e = allow_lds(evict_kernel<PPR>, dyn)) != hipSuccess) return e;
     hipLaunchKernelGGL((evict_kernel<PPR>), grid, dim3(kBlock), dyn, s, a);
+  }
   return hipGetLastError();
 }
 
@@ -513,6 +538,8 @@ hipError_t launch_saliency_t(const EvictArgs& a0, float* out, hipStream_t s) {
   const size_t fixed = (size_t)a.guide_w;
   a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
   const size_t dyn = (fixed + saliency_lds_words(a.n_rows, a.guide_w, fixed)) * sizeof(int);
+  const hipError_t e = allow_lds(saliency_kernel<PPR>, dyn);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(saliency_kernel<PPR>, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out,
                      out == nullptr ? 1 : 0);
   return hipGetLastError();

@@ -307,14 +307,16 @@ def test_layers_entry_points_report_errors():
 
 
 @pytest.mark.parametrize("guide_queue", [binding.LINEAR_QUEUE_LOGITS, binding.LINEAR_QUEUE_QUERIES], ids=["logits", "queries"])
-@pytest.mark.parametrize("budget,lines", [(1608, 203), (1672, 211)], ids=["queue-in-lds", "queue-in-l2"])
-def test_largest_mid_regions(budget, lines, guide_queue):
-    """Mid regions of 1600 candidates (at n = 8 the largest whose guide queue the end-of-line
-    kernel still copies to LDS) and of 1664 (read from global memory instead), with the keys
-    split over two workgroups: two evictions each, oracle on both heads."""
-    w = synth.Workload("largest-mid", 1, 1, 2, 64, 5, 8, lines, budget, 0, 1, "bf16", 33)
+@pytest.mark.parametrize("n,budget,lines", [(8, 1608, 203), (8, 1672, 211), (24, 2088, 89)],
+                         ids=["queue-51KB", "queue-73KB", "queue-196KB"])
+def test_largest_mid_regions(n, budget, lines, guide_queue):
+    """Mid regions of 1600 and 1664 candidates at n = 8 (their line's logits fit the 64 KiB of
+    LDS every device grants, resp. only the 160 KiB of this one) and of 2040 candidates at
+    n = 24 (196 KB: read from global memory instead), with the keys split over several
+    workgroups: two evictions each, oracle on both heads."""
+    w = synth.Workload("largest-mid", 1, 1, 2, 64, 5, n, lines, budget, n if n > 8 else 0, 1, "bf16", 33)
     rep = run_parity(w, all_slices(w), progress=None, guide_queue=guide_queue)
-    say(f"{w.name} B={budget} queue {guide_queue}: {rep}")
+    say(f"{w.name} n={n} B={budget} queue {guide_queue}: {rep}")
     assert rep.evictions == 2 * 2 and rep.steps == w.n_visual
     with pytest.raises(binding.LinearError):      # more than 2048 candidates are refused
         binding.linear_workspace_bytes(binding.cfg_from_workload(
