@@ -165,15 +165,18 @@ bool make_plan(int dtype, int head_dim, int pairs, int target, int force_split, 
   // Wavefronts per workgroup: enough for `target` row groups each, at least as many as the
   // deepest kernel needs, at most what the register budget of the resulting depth allows.
   // Default shape (measured on all five workloads): the deepest wavefronts that still put
-  // about eight wavefronts on every compute unit; few, long wavefronts keep the per-wavefront
-  // prologue and merge small, but a launch with too few of them cannot cover the memory
-  // latency.
+  // about five wavefronts on every compute unit; few, long wavefronts keep the per-wavefront
+  // prologue and merge small (a 12-deep wavefront has 24 KiB of loads in flight), but a launch
+  // with too few of them cannot cover the memory latency.
   int nw;
   if (target > 0) {
     nw = std::max(ceil_div(gps, target), ceil_div(gps, 16));
   } else {
-    const int want_total = 8 * 256;
+    const int want_total = 5 * 256;
     nw = std::max(ceil_div(gps, 16), ceil_div(want_total, pairs * n_split));
+    // wavefronts deeper than 12 row groups (three per SIMD fit) only pay when the launch has
+    // at least eight wavefronts per compute unit anyway
+    if ((int64_t)nw * pairs * n_split < 8 * 256) nw = std::max(nw, ceil_div(gps, 12));
     nw = std::min(nw, gps);
   }
   nw = std::max(1, std::min(16, nw));
