@@ -141,8 +141,8 @@ struct Plan {
   int n_split, rows_per_split, n_waves, depth, new_wave;
 };
 
-bool make_plan(int dtype, int head_dim, int pairs, int target, int force_split, int cached_rows,
-               Plan* p) {
+bool make_plan(int dtype, int head_dim, int pairs, bool stages_logits, int target, int force_split,
+               int cached_rows, Plan* p) {
   const int rpg = linear::decode_rows_per_group(dtype, head_dim);
   const int groups = ceil_div(cached_rows, rpg);
   int n_split = force_split;
@@ -165,14 +165,16 @@ bool make_plan(int dtype, int head_dim, int pairs, int target, int force_split, 
   // Wavefronts per workgroup: enough for `target` row groups each, at least as many as the
   // deepest kernel needs, at most what the register budget of the resulting depth allows.
   // Default shape (measured on all five workloads): the deepest wavefronts that still put
-  // about five wavefronts on every compute unit; few, long wavefronts keep the per-wavefront
-  // prologue and merge small (a 12-deep wavefront has 24 KiB of loads in flight), but a launch
-  // with too few of them cannot cover the memory latency.
+  // about five wavefronts on every compute unit (eight when the step also stages logits for a
+  // guide queue of logits: the wavefront that stores them should not be the one that merges);
+  // few, long wavefronts keep the per-wavefront prologue and merge small (a 12-deep wavefront
+  // has 24 KiB of loads in flight), but a launch with too few of them cannot cover the memory
+  // latency.
   int nw;
   if (target > 0) {
     nw = std::max(ceil_div(gps, target), ceil_div(gps, 16));
   } else {
-    const int want_total = 5 * 256;
+    const int want_total = (stages_logits ? 8 : 5) * 256;
     nw = std::max(ceil_div(gps, 16), ceil_div(want_total, pairs * n_split));
     // wavefronts deeper than 12 row groups (three per SIMD fit) only pay when the launch has
     // at least eight wavefronts per compute unit anyway
@@ -354,7 +356,8 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
   Plan plan;
-  if (!make_plan(c.dtype, c.head_dim, d.pairs, kv->groups_per_wave, kv->force_split, a.t - 1, &plan))
+  if (!make_plan(c.dtype, c.head_dim, d.pairs, d.compresses && !d.queries, kv->groups_per_wave,
+                 kv->force_split, a.t - 1, &plan))
     return LINEAR_EINVAL;
   a.n_split = plan.n_split;
   a.rows_per_split = plan.rows_per_split;
@@ -514,7 +517,8 @@ int linear_plan_shape(const linear_cfg_t* cfg, int32_t cached_keys, int32_t grou
       n_split < 0 || n_split > linear::kMaxSplit)
     return LINEAR_EINVAL;
   Plan p;
-  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, groups_per_wave, n_split, cached_keys, &p))
+  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, d.compresses && !d.queries, groups_per_wave, n_split,
+                 cached_keys, &p))
     return LINEAR_EINVAL;
   shape[0] = p.n_split;
   shape[1] = p.rows_per_split;

@@ -95,15 +95,17 @@ DEPTHS = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16}
 
 
 @pytest.mark.parametrize("name", sorted(synth.WORKLOADS))
-@pytest.mark.parametrize("full", [False, True])
-def test_launch_shape_covers_every_step(name, full):
+@pytest.mark.parametrize("full,guide_queue", [(False, binding.LINEAR_QUEUE_AUTO), (True, binding.LINEAR_QUEUE_AUTO),
+                                             (False, binding.LINEAR_QUEUE_LOGITS)],
+                         ids=["compressed", "full-cache", "compressed-logits-queue"])
+def test_launch_shape_covers_every_step(name, full, guide_queue):
     """Host planner: for every cache length a workload reaches (compressed and full cache),
     the decode kernel's launch shape holds all cached keys, leaves no workgroup empty, uses an
     instantiated depth within the register budget, and names a valid wavefront for the new
     token."""
     w = synth.WORKLOADS[name]
     w = w.full_cache() if full else w
-    cfg = binding.cfg_from_workload(w)
+    cfg = binding.cfg_from_workload(w, guide_queue=guide_queue)
     t_max = w.n_cond + w.budget
     for gpw, ns in ((0, 0), (1, 0), (5, 0), (16, 0), (0, 3), (3, 7)):
         for keys in range(0, t_max):
