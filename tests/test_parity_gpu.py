@@ -332,3 +332,75 @@ def test_lumina_1024_shape_sampled_slices():
     rep = run_parity(w, sl, progress=say, layers_call=True)
     say(f"{w.name}: {rep}")
     assert rep.steps == w.n_visual and rep.evictions == 56 * len(sl)
+
+
+@pytest.mark.parametrize("w", [synth.LLAMAGEN_XL, synth.JANUS_PRO_1B], ids=lambda w: w.name)
+def test_full_size_properties_every_pair(w):
+    """What holds for every (layer, sequence, head) of a full-size image, checked on all of them
+    with library routines (the oracle only replays sampled slices): retained positions ascend,
+    contain the prefix, the anchor and the recent lines, and shrink monotonically (an evicted
+    token never returns); retained K/V rows are bit-identical copies of the inputs at those
+    positions; each attention output equals softmax(q K^T / sqrt(d)) V over the rows the cache
+    held at that step (torch, fp32), at the last step of several lines."""
+    dev = "cuda:0"
+    cache = binding.LineARCache(binding.cfg_from_workload(w), dev)
+    kc, vc = synth.cond_kv(w, dev)
+    cache.start_image(kc, vc)
+    qs, ks, vs = synth.image_qkv(w, dev)                       # [N, L, Bz, H, d]
+    out = torch.empty((w.n_layers, w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
+    n, C, B = w.line_len, w.n_cond, w.budget
+    stride, ostride = qs[0, 0].numel() * qs.element_size(), out[0].numel() * 4
+    check_lines = {1, B // n, B // n + 1, w.n_lines // 2, w.n_lines}
+    layers = sorted({0, w.n_layers // 2, w.n_layers - 1})
+    prev = {l: None for l in layers}
+    scale = 1.0 / w.head_dim ** 0.5
+    for step in range(w.n_visual):
+        line = step // n + 1
+        last_of_line = (step + 1) % n == 0
+        before = None
+        if last_of_line and line in check_lines:
+            # cache rows before the step; the step then appends its own k, v
+            before = {l: cache.gather(l) for l in layers}
+        binding.decode_step_layers(cache.handle, 0, w.n_layers, qs[step].data_ptr(), ks[step].data_ptr(),
+                                   vs[step].data_ptr(), out.data_ptr(), stride, ostride, cache.stream())
+        if before is not None:
+            for l in layers:
+                kg, vg, _ = before[l]
+                K = torch.cat((kg.float(), ks[step, l].float().unsqueeze(2)), dim=2)      # [Bz, H, T, d]
+                V = torch.cat((vg.float(), vs[step, l].float().unsqueeze(2)), dim=2)
+                logits = torch.einsum("bhd,bhtd->bht", qs[step, l].float(), K) * scale
+                ref = torch.einsum("bht,bhtd->bhd", torch.softmax(logits, dim=-1), V)
+                err = (out[l] - ref).abs().max().item()
+                assert err <= 2e-4, f"{w.name}: output differs by {err:.3e} at step {step} layer {l}"
+        if not last_of_line:
+            continue
+        binding.end_of_line_evict_layers(cache.handle, 0, w.n_layers, cache.stream())
+        for l in layers:
+            kg, vg, pg = cache.gather(l)                       # [Bz, H, T, d], [Bz, H, T]
+            T = pg.shape[-1]
+            evicted = B // n <= line <= w.n_lines - 1
+            assert T == C + (B - n if evicted else min(line * n, B))
+            pos = pg.long()
+            assert bool((pos[..., 1:] > pos[..., :-1]).all())
+            head = C + min(w.n_init, line * n)
+            assert bool((pos[..., :head] == torch.arange(head, device=dev)).all())
+            tail = min(w.n_recent_lines * n, line * n)
+            newest = C + line * n - 1
+            assert bool((pos[..., T - tail:] == torch.arange(newest - tail + 1, newest + 1, device=dev)).all())
+            if prev[l] is not None:
+                # every retained position was retained after the previous line or belongs to this line
+                was = torch.zeros((w.batch, w.n_heads, C + w.n_visual), dtype=torch.bool, device=dev)
+                was.scatter_(2, prev[l], True)
+                was[..., C + (line - 1) * n: C + line * n] = True
+                assert bool(was.gather(2, pos).all())
+            prev[l] = pos
+            # rows are copies of the inputs at their positions
+            vis = pos[..., C:] - C                              # [Bz, H, T - C] step index of each visual row
+            kin = ks[:, l].permute(1, 2, 0, 3)                  # [Bz, H, N, d]
+            vin = vs[:, l].permute(1, 2, 0, 3)
+            idx = vis.unsqueeze(-1).expand(-1, -1, -1, w.head_dim)
+            assert torch.equal(kg[..., C:, :], kin.gather(2, idx))
+            assert torch.equal(vg[..., C:, :], vin.gather(2, idx))
+            assert torch.equal(kg[..., :C, :], kc[l]) and torch.equal(vg[..., :C, :], vc[l])
+    torch.cuda.synchronize()
+    cache.close()
