@@ -11,6 +11,7 @@
 // so processing destination rows in ascending tiles -- load the tile's source rows into
 // registers, barrier, store -- never overwrites a row that is still to be read.
 #include "kernels.h"
+#include "lanes.h"
 
 namespace linear {
 namespace {
@@ -18,12 +19,9 @@ namespace {
 constexpr int kPiecesPerThread = 4;   // 16-byte pieces of K (and of V) a thread holds per tile
 constexpr int kMaxWaves = 16;
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float ninf() { return -__builtin_inff(); }
-__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
-
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 
 // Eq. 9's product for one pair when the guide queue holds the queries (Eq. 8 as printed):
 // dst[r][j] = (q_r . k_(mid_lo + j)) * scale * log2(e) for the n_rows queued queries and the mid
@@ -80,6 +78,121 @@ __device__ void fill_logits(const EvictArgs& a, int pair, float* dst, int dst_pi
       }
     }
   }
+}
+
+// Eq. 9 in one pass for the common small case (score mode 0 with a queue of queries, at most
+// 64 mid keys, at most 16 queries per wavefront of the workgroup): wavefront w takes query
+// rows 16 w .. 16 w + 15 against all keys, so a row's logits sit in the MFMA result registers
+// of one 16-lane row (lane l: key (l % 16) of each 16-key tile, queries 4 (l / 16) .. + 3) and
+// its softmax statistics are DPP reductions over that row, no LDS and no barrier; the
+// probabilities are added up over the wavefront's queries (in-lane, then across the four lane
+// rows) and the wavefronts' partial column sums meet in LDS once, added in wavefront order.
+// sc[j] = (1/n) sum over the queued queries of their softmax row at mid key j.  `part` is LDS
+// space for 64 floats per wavefront.  All threads call it; it ends with a barrier.
+constexpr int kSmallKeys = 64;
+__host__ __device__ inline bool saliency_is_small(const EvictArgs& a, int n_threads) {
+  return a.qq != nullptr && a.mid_n <= kSmallKeys && a.n_rows <= 16 * (n_threads / 64);
+}
+template <int PPR, bool BF16>
+__device__ void saliency_small(const EvictArgs& a, int pair, float* part, float* sc) {
+  constexpr int STEPS = PPR / 4;          // 64-byte slices of a row
+  constexpr int NT = kSmallKeys / 16;     // key tiles
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n_waves = blockDim.x >> 6;
+  const int r16 = lane & 15, quarter = lane >> 4;
+  const int n_rows = a.n_rows, n_keys = a.mid_n;
+  const uint4* qq = reinterpret_cast<const uint4*>(a.qq) + (size_t)pair * a.line_len * PPR;
+  const uint4* kc = reinterpret_cast<const uint4*>(a.kc) + ((size_t)pair * a.t_max + a.mid_lo) * PPR;
+  float col[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) col[t] = 0.f;
+  if (wave * 16 < n_rows) {
+    uint4 qa[STEPS], kb[NT][STEPS];
+    const int row = min(wave * 16 + r16, n_rows - 1);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) qa[s] = qq[(size_t)row * PPR + s * 4 + quarter];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int key = min(t * 16 + r16, n_keys - 1);
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s) kb[t][s] = kc[(size_t)key * PPR + s * 4 + quarter];
+    }
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s) {
+        if (BF16) {
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[s]),
+                                                           __builtin_bit_cast(bf16x8, kb[t][s]), acc[t], 0, 0, 0);
+        } else {
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[s].x), __uint_as_float(kb[t][s].x), acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[s].y), __uint_as_float(kb[t][s].y), acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[s].z), __uint_as_float(kb[t][s].z), acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(qa[s].w), __uint_as_float(kb[t][s].w), acc[t], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // query wave*16 + quarter*4 + i: logits in log2 units, keys past the end masked
+      float x[NT], mx = ninf();
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        x[t] = t * 16 + r16 < n_keys ? acc[t][i] * a.scale_log2e : ninf();
+        mx = fmaxf(mx, x[t]);
+      }
+      mx = max_within_row(mx);
+      float sum = 0.f;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        x[t] = ex2(x[t] - mx);
+        sum += x[t];
+      }
+      sum = sum_within<16>(sum);
+      const float inv = wave * 16 + quarter * 4 + i < n_rows ? 1.0f / sum : 0.f;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) col[t] = __builtin_fmaf(x[t], inv, col[t]);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {   // the four lane rows hold four queries each
+      col[t] += __shfl_xor(col[t], 16);
+      col[t] += __shfl_xor(col[t], 32);
+    }
+  }
+  if (quarter == 0) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) part[wave * kSmallKeys + t * 16 + r16] = col[t];
+  }
+  __syncthreads();
+  if (tid < n_keys) {
+    float t = 0.f;
+    for (int w = 0; w < n_waves; ++w) t += part[w * kSmallKeys + tid];
+    sc[tid] = t * (1.0f / (float)a.line_len);
+  }
+  __syncthreads();
+}
+
+// Eq. 10 for at most 64 candidates by one wavefront, no barrier inside: lane j holds candidate
+// j, ranks it against the others by lane broadcasts and takes its slot from the keep mask.
+// Same outputs as select_survivors.  Called by the first wavefront only.
+__device__ void select_small(const float* sc, int m, int n_evict, int* src, int* dst, int* first) {
+  const int j = threadIdx.x & 63;
+  const float sj = j < m ? sc[j] : 0.f;
+  int rank = 0;
+  for (int k = 0; k < m; ++k) {
+    const float sk = lane_bcast(sj, k);
+    rank += (sk < sj) || (sk == sj && k < j);
+  }
+  const bool kp = j < m && rank >= n_evict;
+  const unsigned long long mask = __ballot(kp);
+  const unsigned long long gone = ~mask & (m >= 64 ? ~0ull : (1ull << m) - 1ull);
+  if (j < m) {
+    const int slot = __popcll(mask & ((1ull << j) - 1ull));
+    if (kp && src) src[slot] = j;
+    if (dst) dst[j] = kp ? slot : -1;
+  }
+  if (j == 0) *first = gone ? __builtin_ctzll(gone) : m;
 }
 
 // Column sums of the line's softmax rows for one pair.
@@ -256,8 +369,10 @@ size_t lds_limit_words() {
 inline bool queue_fits_lds(int n_rows, int guide_w, size_t fixed_words) {
   return fixed_words + 2 * (size_t)n_rows + (size_t)n_rows * (guide_w + 2) <= lds_limit_words();
 }
-inline size_t saliency_lds_words(int n_rows, int guide_w, size_t fixed_words) {
-  return 2 * (size_t)n_rows + (queue_fits_lds(n_rows, guide_w, fixed_words) ? (size_t)n_rows * (guide_w + 2) : 0);
+inline size_t saliency_lds_words(const EvictArgs& a, int n_threads, size_t fixed_words, bool small_ok = true) {
+  if (small_ok && saliency_is_small(a, n_threads)) return 2 * (size_t)a.n_rows + (size_t)kSmallKeys * (n_threads / 64);
+  return 2 * (size_t)a.n_rows +
+         (queue_fits_lds(a.n_rows, a.guide_w, fixed_words) ? (size_t)a.n_rows * (a.guide_w + 2) : 0);
 }
 // A kernel that asks for more than the 64 KiB every device grants must be told so first.
 template <class K>
@@ -326,10 +441,18 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
   const int mid_after = m - a.n_evict;
 
   if (tid == 0) sm_first = m;
-  block_saliency<PPR, 2>(a, pair, qs, st, sc);
-  if (a.score_mode == 2) add_accumulated(a, pair, sc);
-  select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
-  if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
+  if (saliency_is_small(a, kBlock)) {
+    float* part = st + 2 * a.n_rows;
+    if (a.elem_bf16) saliency_small<PPR, true>(a, pair, part, sc);
+    else saliency_small<PPR, false>(a, pair, part, sc);
+    if (tid < 64) select_small(sc, m, a.n_evict, src, nullptr, &sm_first);
+    __syncthreads();
+  } else {
+    block_saliency<PPR, 2>(a, pair, qs, st, sc);
+    if (a.score_mode == 2) add_accumulated(a, pair, sc);
+    select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
+    if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
+  }
   SurvivorPositions<kBlock> sp;
   sp.load(a, pair, src);   // its latency overlaps with the first tile's loads
 
@@ -407,10 +530,18 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
     }
   }
   if (tid == 0) sm_first = m;
-  block_saliency<PPR, (PIECES > 4 ? 1 : 2)>(a, pair, qs, st, sc);
-  if (a.score_mode == 2) add_accumulated(a, pair, sc);
-  select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
-  if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
+  if (PIECES <= 4 && saliency_is_small(a, BLOCK)) {   // (the 8-piece instance has no registers to spare)
+    float* part = st + 2 * a.n_rows;
+    if (a.elem_bf16) saliency_small<PPR, true>(a, pair, part, sc);
+    else saliency_small<PPR, false>(a, pair, part, sc);
+    if (tid < 64) select_small(sc, m, a.n_evict, src, dstmap, &sm_first);
+    __syncthreads();
+  } else {
+    block_saliency<PPR, (PIECES > 4 ? 1 : 2)>(a, pair, qs, st, sc);
+    if (a.score_mode == 2) add_accumulated(a, pair, sc);
+    select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
+    if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
+  }
   SurvivorPositions<BLOCK> sp;
   sp.load(a, pair, src);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -439,8 +570,14 @@ __global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, flo
   float* st = sc + a.guide_w;
   float* qs = a.queue_in_lds ? st + 2 * a.n_rows : nullptr;
   const int pair = blockIdx.x;
-  block_saliency<PPR, 2>(a, pair, qs, st, sc);
-  if (a.score_mode == 2) add_accumulated(a, pair, sc);
+  if (saliency_is_small(a, kBlock)) {
+    float* part = st + 2 * a.n_rows;
+    if (a.elem_bf16) saliency_small<PPR, true>(a, pair, part, sc);
+    else saliency_small<PPR, false>(a, pair, part, sc);
+  } else {
+    block_saliency<PPR, 2>(a, pair, qs, st, sc);
+    if (a.score_mode == 2) add_accumulated(a, pair, sc);
+  }
   if (fold) {
     float* acc = a.acc + (size_t)pair * a.guide_w;
     for (int j = threadIdx.x; j < a.n_cols; j += kBlock) acc[j] = sc[j];
@@ -501,18 +638,21 @@ hipError_t launch_evict_t(const EvictArgs& a0, hipStream_t s) {
   EvictArgs a = a0;
   const size_t fixed = (size_t)a.guide_w + 2 * (size_t)a.mid_n;
   a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
-  const size_t dyn = (fixed + saliency_lds_words(a.n_rows, a.guide_w, fixed)) * sizeof(int);
   const dim3 grid((unsigned)a.n_pairs);
   const int64_t pieces = (int64_t)(a.mid_n + a.n_tail) * PPR;
   // Measured on the five workloads: with at least two pairs per compute unit the tiled
   // kernel wins (it never reads the evicted rows); with fewer pairs than that and more than
   // one tile of rows (Lumina: 256 pairs, 245 rows of 256 B) the register-resident kernel with
   // 16 wavefronts per pair is 1.5x faster.
+  const bool fast4 = a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4;
+  const bool fast8 = a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8;
+  const int threads = fast4 || fast8 ? 1024 : kBlock;
+  const size_t dyn = (fixed + saliency_lds_words(a, threads, fixed, !fast8)) * sizeof(int);
   hipError_t e;
-  if (a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4) {
+  if (fast4) {
     if ((e = allow_lds(evict_fast_kernel<PPR, 4, 1024>, dyn)) != hipSuccess) return e;
     hipLaunchKernelGGL((evict_fast_kernel<PPR, 4, 1024>), grid, dim3(1024), dyn, s, a);
-  } else if (a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8) {
+  } else if (fast8) {
     if ((e = allow_lds(evict_fast_kernel<PPR, 8, 1024>, dyn)) != hipSuccess) return e;
     hipLaunchKernelGGL((evict_fast_kernel<PPR, 8, 1024>), grid, dim3(1024), dyn, s, a);
   } else {
@@ -537,7 +677,7 @@ hipError_t launch_saliency_t(const EvictArgs& a0, float* out, hipStream_t s) {
   EvictArgs a = a0;
   const size_t fixed = (size_t)a.guide_w;
   a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
-  const size_t dyn = (fixed + saliency_lds_words(a.n_rows, a.guide_w, fixed)) * sizeof(int);
+  const size_t dyn = (fixed + saliency_lds_words(a, kBlock, fixed)) * sizeof(int);
   const hipError_t e = allow_lds(saliency_kernel<PPR>, dyn);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(saliency_kernel<PPR>, dim3((unsigned)a.n_pairs), dim3(kBlock), dyn, s, a, out,
