@@ -338,13 +338,15 @@ struct SurvivorPositions {
       }
     }
   }
+  // A pair's map is a whole number of aligned 128-byte lines and all of them are written
+  // (padding included), so no line is written in part.
   __device__ __forceinline__ void store(const EvictArgs& a, int pair) const {
     int32_t* map = a.pos + (size_t)pair * a.pos_pitch;
     const int mid_after = a.mid_n - a.n_evict;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int d = i * BLOCK + (int)threadIdx.x;
-      if (d < mid_after) map[d] = pv[i];
+      if (d < a.pos_pitch) __builtin_nontemporal_store(d < mid_after ? pv[i] : 0, &map[d]);
     }
   }
 };

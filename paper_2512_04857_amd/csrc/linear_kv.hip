@@ -90,7 +90,7 @@ int derive(const linear_cfg_t& c, Derived* d) {
   // Original positions are kept only for the survivors of evictions, mid_n - n per pair: every
   // other row's position follows from its index (prefix and anchor in front, whole consecutive
   // lines behind).
-  d->pos_pitch = d->compresses ? std::max(1, d->mid_n - c.line_len) : 1;
+  d->pos_pitch = d->compresses ? (std::max(1, d->mid_n - c.line_len) + 31) / 32 * 32 : 32;   // whole 128-byte lines
   d->pos_layer = P * (size_t)d->pos_pitch;
   size_t off = 0;
   d->off_guide = off;    off = align_up(off + P * d->guide_pair * (d->queries ? 1 : c.n_layers) * sizeof(float));
