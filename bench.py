@@ -95,7 +95,7 @@ class Runner:
         self.stride = self.q[0, 0].numel() * self.q.element_size()
         self.ostride = self.out[0].numel() * 4
 
-    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0, score_mode=0, guide_queue=0):
+    def run(self, wl, steps, warmup, groups_per_wave=0, n_split=0, score_mode=0, guide_queue=0, fused_rope=False):
         """Times `steps` decode steps of workload variant `wl` (same shapes, its own budget)
         from the start of an image.  Returns a dict of measurements."""
         torch, binding = self.torch, self.binding
@@ -104,6 +104,13 @@ class Runner:
                                     self.device)
         lib = binding.lib()
         dsteps, evicts = lib.decode_step_layers, lib.end_of_line_evict_layers
+        if fused_rope:
+            # the rotary embedding fused into the step: the pre-generated q, k stand in for unrotated
+            # ones (the timing does not depend on the values); one table row per position
+            from paper_2512_04857_amd import synth
+            table = torch.stack([synth.rope_cos_sin(wl, wl.n_cond + i, self.device) for i in range(wl.n_visual)])
+            tb, tst = table.data_ptr(), table[0].numel() * 4
+            rope = lib.decode_step_rope_layers
         qb, kb, vb, ob = self.q.data_ptr(), self.k.data_ptr(), self.v.data_ptr(), self.out.data_ptr()
         st, ost = self.stride, self.ostride
         stream = cache.stream()
@@ -119,7 +126,10 @@ class Runner:
                 events[-1][1].record()
             for s in range(n_steps):
                 off = s * L * st
-                rc = dsteps(h, 0, L, qb + off, kb + off, vb + off, ob, st, ost, stream)
+                if fused_rope:
+                    rc = rope(h, 0, L, qb + off, kb + off, vb + off, tb + s * tst, ob, st, ost, stream)
+                else:
+                    rc = dsteps(h, 0, L, qb + off, kb + off, vb + off, ob, st, ost, stream)
                 if rc:
                     raise binding.LinearError(rc, "decode_step_layers")
                 if (s + 1) % n == 0:
@@ -246,6 +256,8 @@ def main():
                     help="0 = Eq. 9 as printed (default), 1 = decode-softmax mass, 2 = accumulated attention")
     ap.add_argument("--guide-queue", type=int, default=0,
                     help="0: automatic; 1: the guide queue holds logits; 2: it holds the queries (score mode 0 only)")
+    ap.add_argument("--fused-rope", action="store_true",
+                    help="time decode_step_rope (rotary embedding of q and k fused into the step)")
     ap.add_argument("--groups-per-wave", type=int, default=0, help="decode kernel tuning (0 = default)")
     ap.add_argument("--n-split", type=int, default=0, help="decode kernel tuning (0 = automatic)")
     args = ap.parse_args()
@@ -287,7 +299,8 @@ def main():
         log(f"calibration pass (uint8 add kernel): {args.calibrate_copy_mib} MiB read + "
             f"{args.calibrate_copy_mib} MiB written")
         del src, dst
-    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split, args.score_mode, args.guide_queue)
+    comp = r.run(w, steps, args.warmup, args.groups_per_wave, args.n_split, args.score_mode, args.guide_queue,
+                 args.fused_rope)
     log("compressed:", json.dumps(comp))
     full = None if args.skip_full else r.run(w.full_cache(), steps, args.warmup, args.groups_per_wave, args.n_split)
     if full:
@@ -310,7 +323,7 @@ def main():
         "config": {"workload": w.name, "n_layers": w.n_layers, "sequences": w.batch, "n_heads": w.n_heads,
                    "head_dim": w.head_dim, "n_cond": w.n_cond, "grid": f"{w.n_lines}x{w.line_len}",
                    "budget": w.budget, "n_init": w.n_init, "n_recent_lines": w.n_recent_lines,
-                   "score_mode": args.score_mode, "guide_queue": args.guide_queue,
+                   "score_mode": args.score_mode, "guide_queue": args.guide_queue, "fused_rope": args.fused_rope,
                    "launches": "one decode kernel per layer per token, one eviction kernel per layer per line, "
                                "enqueued back to back on one stream (decode_step_layers), no graph"},
         "whole_image_ms": round(comp["total_ms"], 3) if steps == w.n_visual else None,

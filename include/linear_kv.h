@@ -126,6 +126,24 @@ LINEAR_API int decode_step_layers(linear_kv_t* kv, int32_t first_layer, int32_t 
                        const void* k, const void* v, void* out, size_t qkv_stride,
                        size_t out_stride, void* stream);
 
+/* decode_step with the rotary position embedding of the new token fused in (the producer side
+ * of Eq. 2-4: the paper's models rotate q and k before attention).  q and k arrive as the
+ * projection leaves them, NOT rotated; the step rotates both in fp32 (element t paired with
+ * t + d/2: x'_t = x_t cos_t - x_(t+d/2) sin_t, x'_(t+d/2) = x_t sin_t + x_(t+d/2) cos_t, every
+ * product and sum rounded separately), rounds to the storage type, attends with the rotated q
+ * and appends the rotated k; v is used as is.
+ *   cos_sin : DEVICE [d] float, 16-byte aligned: the d/2 cosines, then the d/2 sines, of the
+ *             pair angles at the new token's position; read during the step only.
+ * Everything else as decode_step. */
+LINEAR_API int decode_step_rope(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
+                     const float* cos_sin, void* out, void* stream);
+
+/* decode_step_rope for `count` consecutive layers (one position, so one cos_sin row); strides
+ * and error behaviour as decode_step_layers. */
+LINEAR_API int decode_step_rope_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, const void* q,
+                            const void* k, const void* v, const float* cos_sin, void* out,
+                            size_t qkv_stride, size_t out_stride, void* stream);
+
 /* End of a raster line of one layer (Sec. 3.3; Eq. 5-7 and 10).  Must follow exactly n
  * decode_step calls.  On lines B/n .. h-1 it evicts, independently per (sequence, head),
  * the n mid tokens with the smallest saliency (ties: older token first) and compacts K, V and

@@ -18,6 +18,7 @@ LINEAR_F32, LINEAR_BF16 = 0, 1
 LINEAR_QUEUE_AUTO, LINEAR_QUEUE_LOGITS, LINEAR_QUEUE_QUERIES = 0, 1, 2
 
 EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_layers",
+           "decode_step_rope", "decode_step_rope_layers",
            "end_of_line_evict", "end_of_line_evict_layers", "kv_scores",
            "kv_gather", "kv_length", "linear_set_tuning", "linear_plan_shape", "kv_free", "linear_strerror",
            "linear_last_hip_error")
@@ -57,6 +58,8 @@ def lib() -> C.CDLL:
                               C.POINTER(vp), vp, C.POINTER(vp)]
         L.decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.decode_step_layers.argtypes = [vp, i32, i32, vp, vp, vp, vp, C.c_size_t, C.c_size_t, vp]
+        L.decode_step_rope.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        L.decode_step_rope_layers.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, C.c_size_t, C.c_size_t, vp]
         L.end_of_line_evict.argtypes = [vp, i32, vp]
         L.end_of_line_evict_layers.argtypes = [vp, i32, i32, vp]
         L.kv_scores.argtypes = [vp, i32, vp, C.POINTER(i32), vp]
@@ -125,6 +128,20 @@ def decode_step_layers(kv: int, first_layer: int, count: int, q: int, k: int, v:
     rc = lib().decode_step_layers(kv, first_layer, count, q, k, v, out, qkv_stride, out_stride, stream)
     if rc:
         raise LinearError(rc, "decode_step_layers")
+
+
+def decode_step_rope(kv: int, layer: int, q: int, k: int, v: int, cos_sin: int, out: int, stream: int = 0) -> None:
+    rc = lib().decode_step_rope(kv, layer, q, k, v, cos_sin, out, stream)
+    if rc:
+        raise LinearError(rc, "decode_step_rope")
+
+
+def decode_step_rope_layers(kv: int, first_layer: int, count: int, q: int, k: int, v: int, cos_sin: int,
+                            out: int, qkv_stride: int, out_stride: int, stream: int = 0) -> None:
+    rc = lib().decode_step_rope_layers(kv, first_layer, count, q, k, v, cos_sin, out, qkv_stride, out_stride,
+                                       stream)
+    if rc:
+        raise LinearError(rc, "decode_step_rope_layers")
 
 
 def end_of_line_evict_layers(kv: int, first_layer: int, count: int, stream: int = 0) -> None:

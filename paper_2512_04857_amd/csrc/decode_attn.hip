@@ -111,12 +111,64 @@ __device__ __forceinline__ void merge_partials(const float* pm, const float* pl,
   }
 }
 
+// Rotary embedding of one row held as LPR pieces of 16 bytes, element t paired with t + d/2:
+// lane `seg` holds elements seg*EPL .. seg*EPL + EPL-1, its partner elements sit LPR/2 lanes
+// away.  x' = x cos + sign * partner sin with sign -1 in the first half and +1 in the second,
+// each product and the sum rounded to fp32 separately (no fused multiply-add) and the result
+// rounded to the storage type, so that the rotated row has the bits an unfused fp32
+// implementation produces.  `cs` points at this lane's EPL cosines, `sn` at its EPL sines.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_u32(unsigned x) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+template <int LPR>
+__device__ __forceinline__ uint4 partner_piece(const uint4& r) {
+  uint4 p;
+  if (LPR == 8) {          // row_ror:4 -- every 16-lane row holds two copies of the 8-piece row
+    p.x = dpp_u32<0x124>(r.x); p.y = dpp_u32<0x124>(r.y); p.z = dpp_u32<0x124>(r.z); p.w = dpp_u32<0x124>(r.w);
+  } else if (LPR == 16) {  // row_ror:8
+    p.x = dpp_u32<0x128>(r.x); p.y = dpp_u32<0x128>(r.y); p.z = dpp_u32<0x128>(r.z); p.w = dpp_u32<0x128>(r.w);
+  } else {                 // 32 lanes per row: the partner is 16 lanes away
+    p.x = __shfl_xor(r.x, 16); p.y = __shfl_xor(r.y, 16); p.z = __shfl_xor(r.z, 16); p.w = __shfl_xor(r.w, 16);
+  }
+  return p;
+}
+__device__ __forceinline__ float rot1(float x, float partner, float c, float s, float sign) {
+#pragma clang fp contract(off)   // two rounded products, then a rounded sum: never a fused multiply-add
+  const float xc = x * c;
+  const float ps = partner * s;
+  return xc + sign * ps;
+}
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  bf16x2_t v = {(__bf16)lo, (__bf16)hi};   // round to nearest even
+  return __builtin_bit_cast(unsigned, v);
+}
+template <bool BF16, int LPR, int EPL>
+__device__ __forceinline__ uint4 rotate_row(const uint4& r, const float (&cc)[EPL], const float (&ss)[EPL], float sign) {
+  const uint4 p = partner_piece<LPR>(r);
+  const unsigned rw[4] = {r.x, r.y, r.z, r.w}, pw[4] = {p.x, p.y, p.z, p.w};
+  unsigned ow[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (BF16) {
+      const float lo = rot1(__uint_as_float(rw[j] << 16), __uint_as_float(pw[j] << 16), cc[2 * j], ss[2 * j], sign);
+      const float hi = rot1(__uint_as_float(rw[j] & 0xffff0000u), __uint_as_float(pw[j] & 0xffff0000u),
+                            cc[(2 * j + 1) % EPL], ss[(2 * j + 1) % EPL], sign);
+      ow[j] = pack_bf16(lo, hi);
+    } else {
+      ow[j] = __float_as_uint(rot1(__uint_as_float(rw[j]), __uint_as_float(pw[j]), cc[j % EPL], ss[j % EPL], sign));
+    }
+  }
+  return make_uint4(ow[0], ow[1], ow[2], ow[3]);
+}
+
 template <int U>
 struct MaxWaves {   // waves per workgroup the register budget of a U-deep wavefront allows
   static constexpr int value = U <= 8 ? 16 : (U <= 12 ? 12 : 8);
 };
 
-template <bool BF16, int D, int U>
+template <bool BF16, int D, int U, bool ROPE>
 __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(const DecodeArgs a) {
   using E = Elems<BF16>;
   constexpr int EPL = E::kPerLane;   // elements per lane
@@ -149,9 +201,19 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   const char* kbase = static_cast<const char*>(a.kc) + ((size_t)pair * a.t_max + r0) * kRowBytes;
   const char* vbase = static_cast<const char*>(a.vc) + ((size_t)pair * a.t_max + r0) * kRowBytes;
   const unsigned in_off = (unsigned)seg * 16u;
-  const uint4 qr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.q) + (size_t)pair * kRowBytes + in_off);
-  const uint4 knr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.k_new) + (size_t)pair * kRowBytes + in_off);
+  uint4 qr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.q) + (size_t)pair * kRowBytes + in_off);
+  uint4 knr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.k_new) + (size_t)pair * kRowBytes + in_off);
   const uint4 vnr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.v_new) + (size_t)pair * kRowBytes + in_off);
+  float rc[EPL], rs[EPL];   // this lane's rotary cosines and sines: requested ahead of the cache rows
+  if (ROPE) {
+    const float* cs = a.cos_sin + (seg * EPL) % (D / 2);
+#pragma unroll
+    for (int j = 0; j < EPL; j += 4) {
+      const float4 c4 = *reinterpret_cast<const float4*>(cs + j), s4 = *reinterpret_cast<const float4*>(cs + D / 2 + j);
+      rc[j] = c4.x; rc[j + 1] = c4.y; rc[j + 2] = c4.z; rc[j + 3] = c4.w;
+      rs[j] = s4.x; rs[j + 1] = s4.y; rs[j + 2] = s4.z; rs[j + 3] = s4.w;
+    }
+  }
   uint4 kr[U], vr[U];
   int row[U];
   unsigned off[U];
@@ -169,6 +231,14 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
   // hold back the rest of the requests for a full memory round trip.
   __builtin_amdgcn_sched_barrier(0);
 
+  if (ROPE) {
+    // q and k of the new token arrive unrotated: every lane rotates its piece of both (all
+    // wavefronts need q; k is only used by the lane group that appends it, but rotating it
+    // everywhere keeps the code straight-line and costs no memory traffic).
+    const float sign = seg < LPR / 2 ? -1.0f : 1.0f;
+    qr = rotate_row<BF16, LPR, EPL>(qr, rc, rs, sign);
+    knr = rotate_row<BF16, LPR, EPL>(knr, rc, rs, sign);
+  }
   // Stores go out as early as their data exists: a kernel ends only when its last store has
   // been acknowledged, so a store issued near the end adds its whole latency to the step.
   if (owner) {
@@ -309,7 +379,8 @@ hipError_t launch_main(const DecodeArgs& a, hipStream_t s) {
   const int workers = a.n_waves * RPW;
   const size_t dyn = ((size_t)workers * (D + 1) + a.n_waves + (size_t)a.mid_n) * sizeof(float);
   const dim3 grid((unsigned)a.n_pairs, (unsigned)a.n_split), block(64u * (unsigned)a.n_waves);
-  hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U>), grid, block, dyn, s, a);
+  if (a.cos_sin) hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U, true>), grid, block, dyn, s, a);
+  else hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U, false>), grid, block, dyn, s, a);
   return hipGetLastError();
 }
 

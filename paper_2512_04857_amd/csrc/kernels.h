@@ -15,6 +15,9 @@ struct DecodeArgs {
   const void* q;      // [P, d] elem
   const void* k_new;  // [P, d] elem
   const void* v_new;  // [P, d] elem
+  const float* cos_sin;  // null, or [d] floats: q and k_new arrive unrotated and are rotated here
+                         //   (rotary embedding, element t paired with t + d/2): cos of the d/2
+                         //   pair angles of the new token's position, then their sines
   void* kc;           // [P, t_max, d] elem
   void* vc;           // [P, t_max, d] elem
   float* out;         // [P, d]

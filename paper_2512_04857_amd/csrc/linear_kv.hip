@@ -325,8 +325,13 @@ int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* const* v_cache,
   return LINEAR_OK;
 }
 
-int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
-                void* out, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// One decode step of one layer; `cos_sin` is null when q and k arrive rotated.
+int decode_step_impl(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
+                     const float* cos_sin, void* out, void* stream) {
   if (!kv || !q || !k || !v || !out) return LINEAR_ENULL;
   if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return LINEAR_EALIGN;
@@ -342,6 +347,7 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   a.q = q;
   a.k_new = k;
   a.v_new = v;
+  a.cos_sin = cos_sin;
   a.kc = kv->k_cache[layer];
   a.vc = kv->v_cache[layer];
   a.out = static_cast<float*>(out);
@@ -392,6 +398,38 @@ int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, co
   return LINEAR_OK;
 }
 
+int decode_layers_impl(linear_kv_t* kv, int32_t first_layer, int32_t count, const void* q, const void* k,
+                       const void* v, const float* cos_sin, void* out, size_t qkv_stride,
+                       size_t out_stride, void* stream) {
+  if (!kv || !q || !k || !v || !out) return LINEAR_ENULL;
+  if (count < 0 || first_layer < 0 || (int64_t)first_layer + count > kv->cfg.n_layers) return LINEAR_EINVAL;
+  if ((qkv_stride | out_stride) & 15u) return LINEAR_EALIGN;
+  for (int32_t i = 0; i < count; ++i) {
+    const int rc = decode_step_impl(kv, first_layer + i, static_cast<const char*>(q) + i * qkv_stride,
+                                    static_cast<const char*>(k) + i * qkv_stride,
+                                    static_cast<const char*>(v) + i * qkv_stride, cos_sin,
+                                    static_cast<char*>(out) + i * out_stride, stream);
+    if (rc != LINEAR_OK) return rc;
+  }
+  return LINEAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
+                void* out, void* stream) {
+  return decode_step_impl(kv, layer, q, k, v, nullptr, out, stream);
+}
+
+int decode_step_rope(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
+                     const float* cos_sin, void* out, void* stream) {
+  if (!cos_sin) return LINEAR_ENULL;
+  if (misaligned(cos_sin)) return LINEAR_EALIGN;
+  return decode_step_impl(kv, layer, q, k, v, cos_sin, out, stream);
+}
+
 int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
   if (!kv) return LINEAR_ENULL;
   if (layer < 0 || layer >= kv->cfg.n_layers) return LINEAR_EINVAL;
@@ -423,17 +461,15 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
 int decode_step_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, const void* q,
                        const void* k, const void* v, void* out, size_t qkv_stride,
                        size_t out_stride, void* stream) {
-  if (!kv || !q || !k || !v || !out) return LINEAR_ENULL;
-  if (count < 0 || first_layer < 0 || (int64_t)first_layer + count > kv->cfg.n_layers) return LINEAR_EINVAL;
-  if ((qkv_stride | out_stride) & 15u) return LINEAR_EALIGN;
-  for (int32_t i = 0; i < count; ++i) {
-    const int rc = decode_step(kv, first_layer + i, static_cast<const char*>(q) + i * qkv_stride,
-                               static_cast<const char*>(k) + i * qkv_stride,
-                               static_cast<const char*>(v) + i * qkv_stride,
-                               static_cast<char*>(out) + i * out_stride, stream);
-    if (rc != LINEAR_OK) return rc;
-  }
-  return LINEAR_OK;
+  return decode_layers_impl(kv, first_layer, count, q, k, v, nullptr, out, qkv_stride, out_stride, stream);
+}
+
+int decode_step_rope_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, const void* q,
+                            const void* k, const void* v, const float* cos_sin, void* out,
+                            size_t qkv_stride, size_t out_stride, void* stream) {
+  if (!cos_sin) return LINEAR_ENULL;
+  if (misaligned(cos_sin)) return LINEAR_EALIGN;
+  return decode_layers_impl(kv, first_layer, count, q, k, v, cos_sin, out, qkv_stride, out_stride, stream);
 }
 
 int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, void* stream) {

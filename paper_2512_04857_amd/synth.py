@@ -139,6 +139,31 @@ def step_qkv(w: Workload, step: int, device="cpu", seed: int = BASE_SEED):
     return q.to(dt).contiguous(), k.to(dt).contiguous(), v.to(dt).contiguous()
 
 
+def rope_cos_sin(w: Workload, position: int, device="cpu") -> torch.Tensor:
+    """Rotary table row for one absolute position: [d] fp32, the d/2 cosines then the d/2 sines
+    of the pair angles position * theta^(-2t/d) (the values `rope` multiplies by)."""
+    d = w.head_dim
+    t = torch.arange(d // 2, device=device, dtype=torch.float64)
+    ang = float(position) * ROPE_THETA ** (-2.0 * t / d)
+    return torch.cat((ang.cos(), ang.sin())).to(torch.float32).contiguous()
+
+
+def step_qkv_unrotated(w: Workload, step: int, device="cpu", seed: int = BASE_SEED):
+    """The same draw as step_qkv, handed over the way a model's projection leaves it: q, k, v
+    rounded to the storage type and NOT rotated, plus what a rotation in fp32 of those rounded
+    values gives, rounded again (q_rot, k_rot) -- the values a consumer that fuses the rotary
+    embedding must reproduce.  Returns (q, k, v, q_rot, k_rot), each [L, Bz, H, d]."""
+    g = _generator(device, seed, w.index, 0x51, step)
+    shape = (3, w.n_layers, w.batch, w.n_heads, 1, w.head_dim)
+    dt = w.torch_dtype
+    x = torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(dt)
+    pos = torch.tensor([w.n_cond + step], device=device)
+    q_rot = rope(x[0].to(torch.float32), pos).to(dt)[..., 0, :]
+    k_rot = rope(x[1].to(torch.float32), pos).to(dt)[..., 0, :]
+    return (x[0][..., 0, :].contiguous(), x[1][..., 0, :].contiguous(), x[2][..., 0, :].contiguous(),
+            q_rot.contiguous(), k_rot.contiguous())
+
+
 def image_qkv(w: Workload, device="cpu", seed: int = BASE_SEED, steps: int | None = None):
     """All steps of one image stacked: three tensors [N, L, Bz, H, d]."""
     n = w.n_visual if steps is None else steps

@@ -66,7 +66,8 @@ class ParityReport:
 
 
 def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, groups_per_wave=0, n_split=0, steps=None,
-               seed=synth.BASE_SEED, check_scores=True, progress=None, layers_call=False) -> ParityReport:
+               seed=synth.BASE_SEED, check_scores=True, progress=None, layers_call=False,
+               fused_rope=False) -> ParityReport:
     """Runs workload `w` on the GPU at its full shape and the oracle on `slices`
     ((layer, sequence, head) triples).  Raises AssertionError on disagreement."""
     o = oracle()
@@ -94,14 +95,29 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, group
     compresses = w.budget < w.n_visual
     mid_n = w.budget - w.n_init - w.n_recent_lines * n
     for step in range(N):
-        q, k, v = synth.step_qkv(w, step, device, seed)
-        if layers_call:     # the multi-layer entry points, as the benchmark uses them
-            binding.decode_step_layers(cache.handle, 0, w.n_layers, q.data_ptr(), k.data_ptr(), v.data_ptr(),
-                                       out.data_ptr(), q[0].numel() * q.element_size(), out[0].numel() * 4,
-                                       cache.stream())
+        if fused_rope:
+            # the library rotates q and k itself; the oracle gets what an unfused fp32 rotation of
+            # the same unrotated values gives (computed by the input generator)
+            q_in, k_in, v, q, k = synth.step_qkv_unrotated(w, step, device, seed)
+            cs = synth.rope_cos_sin(w, w.n_cond + step, device)
+            if layers_call:
+                binding.decode_step_rope_layers(cache.handle, 0, w.n_layers, q_in.data_ptr(), k_in.data_ptr(),
+                                                v.data_ptr(), cs.data_ptr(), out.data_ptr(),
+                                                q[0].numel() * q.element_size(), out[0].numel() * 4,
+                                                cache.stream())
+            else:
+                for l in range(w.n_layers):
+                    binding.decode_step_rope(cache.handle, l, q_in[l].data_ptr(), k_in[l].data_ptr(),
+                                             v[l].data_ptr(), cs.data_ptr(), out[l].data_ptr(), cache.stream())
         else:
-            for l in range(w.n_layers):
-                cache.decode_step(l, q[l], k[l], v[l], out[l])
+            q, k, v = synth.step_qkv(w, step, device, seed)
+            if layers_call:     # the multi-layer entry points, as the benchmark uses them
+                binding.decode_step_layers(cache.handle, 0, w.n_layers, q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                           out.data_ptr(), q[0].numel() * q.element_size(), out[0].numel() * 4,
+                                           cache.stream())
+            else:
+                for l in range(w.n_layers):
+                    cache.decode_step(l, q[l], k[l], v[l], out[l])
         line_q.append(q[li, bi, hi])
         line_k.append(k[li, bi, hi])
         line_v.append(v[li, bi, hi])

@@ -77,6 +77,10 @@ def test_null_and_alignment_errors_without_touching_the_gpu():
     assert L.kv_init(ctypes.byref(cfg), two, odd, 4096, two, two, None, ctypes.byref(h)) == binding.LINEAR_EALIGN
     assert L.kv_init(ctypes.byref(cfg), two, two, 4100, two, two, None, ctypes.byref(h)) == binding.LINEAR_EALIGN
     assert L.decode_step(None, 0, 16, 16, 16, 16, None) == binding.LINEAR_ENULL
+    assert L.decode_step_rope(None, 0, 16, 16, 16, 16, 16, None) == binding.LINEAR_ENULL
+    assert L.decode_step_rope(8, 0, 16, 16, 16, None, 16, None) == binding.LINEAR_ENULL      # no table
+    assert L.decode_step_rope(8, 0, 16, 16, 16, 20, 16, None) == binding.LINEAR_EALIGN       # table not 16-byte aligned
+    assert L.decode_step_rope_layers(8, 0, 1, 16, 16, 16, None, 16, 128, 256, None) == binding.LINEAR_ENULL
     assert L.end_of_line_evict(None, 0, None) == binding.LINEAR_ENULL
     assert L.kv_gather(None, 0, None, None, None, None, None) == binding.LINEAR_ENULL
     assert L.kv_free(None) == binding.LINEAR_OK

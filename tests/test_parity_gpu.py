@@ -84,6 +84,28 @@ def test_logits_queue_every_slice(w, gpw, n_split):
     assert rep.steps == w.n_visual
 
 
+# The rotary embedding fused into the step: q and k go in unrotated, the oracle receives an
+# unfused fp32 rotation of the same values from the input generator.  bf16 and fp32, 8 / 16 / 32
+# lanes per row, one and several workgroups per pair; the retained K rows must come back with
+# exactly the generator's bits.
+@pytest.mark.parametrize("w,gpw,n_split,score_mode", [
+    (synth.TINY_B, 0, 0, 0), (MID_SPLIT, 0, 0, 0), (MID_SPLIT, 3, 2, 1), (LUMINA_SLICE, 4, 5, 0),
+    (F32_R2, 2, 2, 0), (F32_D64_LONG, 0, 0, 2), (NO_COND, 1, 0, 0), (STREAMING, 0, 0, 0),
+], ids=lambda x: getattr(x, "name", str(x)))
+def test_fused_rope_every_slice(w, gpw, n_split, score_mode):
+    rep = run_parity(w, all_slices(w), groups_per_wave=gpw, n_split=n_split, score_mode=score_mode,
+                     fused_rope=True)
+    say(f"{w.name} fused rope, groups/wave {gpw} splits {n_split} mode {score_mode}: {rep}")
+    assert rep.steps == w.n_visual
+
+
+def test_full_size_fused_rope_sampled_slices():
+    w = synth.LLAMAGEN_XL
+    rep = run_parity(w, _sample(w, n_heads=2), layers_call=True, fused_rope=True)
+    say(f"{w.name} fused rope: {rep}")
+    assert rep.steps == w.n_visual and rep.evictions == 20 * len(_sample(w, n_heads=2))
+
+
 def _sample(w, n_heads=4):
     heads = sorted({0, w.n_heads // 3, w.n_heads // 2, w.n_heads - 1})[:n_heads]
     return sampled_slices(w, sorted({0, w.n_layers - 1}), sorted({0, w.batch - 1}), heads)
