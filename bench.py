@@ -198,8 +198,8 @@ class Runner:
             "us_per_step_last_half": last,
             "decode_launches": launches,
             "decode_us_per_launch": decode_ms * 1e3 / launches,
-            "evict_launches": len(evict_lines) * L,
-            "evict_us_per_launch": (evict_ms * 1e3 / (len(evict_lines) * L)) if evict_lines else None,
+            "evict_layer_lines": len(evict_lines) * L,      # evictions of one layer; layers share launches
+            "evict_us_per_layer": (evict_ms * 1e3 / (len(evict_lines) * L)) if evict_lines else None,
             "kv_bytes_per_launch": keys * tok_bytes / steps,
             "kv_bytes_total": keys * tok_bytes * L,
             "mean_keys": keys / steps,
@@ -324,12 +324,13 @@ def main():
                    "head_dim": w.head_dim, "n_cond": w.n_cond, "grid": f"{w.n_lines}x{w.line_len}",
                    "budget": w.budget, "n_init": w.n_init, "n_recent_lines": w.n_recent_lines,
                    "score_mode": args.score_mode, "guide_queue": args.guide_queue, "fused_rope": args.fused_rope,
-                   "launches": "one decode kernel per layer per token, one eviction kernel per layer per line, "
-                               "enqueued back to back on one stream (decode_step_layers), no graph"},
+                   "launches": "one decode kernel per layer per token (decode_step_layers), one eviction kernel "
+                               "per line for all layers (end_of_line_evict_layers), enqueued back to back on one "
+                               "stream, no graph"},
         "whole_image_ms": round(comp["total_ms"], 3) if steps == w.n_visual else None,
         "us_per_step_first_half": comp["us_per_step_first_half"],
         "us_per_step_last_half": comp["us_per_step_last_half"],
-        "evict_us_per_launch": comp["evict_us_per_launch"],
+        "evict_us_per_layer": comp["evict_us_per_layer"],
         "evict_share": round(comp["evict_ms"] / comp["total_ms"], 4),
         "host_wall_ms": round(comp["host_wall_ms"], 1),
         "roofline": {

@@ -153,7 +153,10 @@ LINEAR_API int decode_step_rope_layers(linear_kv_t* kv, int32_t first_layer, int
  * LINEAR_ESTATE in the middle of a line. */
 LINEAR_API int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream);
 
-/* end_of_line_evict for layers first_layer .. first_layer + count - 1, enqueued back to back. */
+/* end_of_line_evict for layers first_layer .. first_layer + count - 1.  The evictions of
+ * different layers do not depend on one another, so layers that are in the same state (the
+ * usual case: every layer has just finished the same line) share kernel launches, up to 48
+ * layers each; otherwise the calls are enqueued one by one, stopping at the first error. */
 LINEAR_API int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, void* stream);
 
 /* Saliency of the current line so far (Eq. 9): S[j] for the mid candidates, averaged over

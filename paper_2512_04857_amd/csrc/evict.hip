@@ -427,8 +427,23 @@ __device__ void select_survivors(const float* sc, int m, int n_evict, int* src, 
   }
 }
 
+// The arguments of layer blockIdx.y of a launch that covers several layers.
+__device__ __forceinline__ EvictArgs layer_args(const EvictArgs& a0, const EvictLayers& ly) {
+  EvictArgs a = a0;
+  const int i = blockIdx.y;
+  a.kc = ly.kc[i];
+  a.vc = ly.vc[i];
+  a.guide += i * ly.guide_stride;
+  a.guide_out += i * ly.guide_stride;
+  if (a.qq) a.qq = static_cast<const char*>(a.qq) + i * ly.qq_stride;
+  a.pos += i * ly.pos_stride;
+  a.acc += i * ly.acc_stride;
+  return a;
+}
+
 template <int PPR>  // 16-byte pieces per key row
-__global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
+__global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a0, const EvictLayers ly) {
+  const EvictArgs a = layer_args(a0, ly);
   extern __shared__ int sm_raw[];
   const int m = a.mid_n, w = a.guide_w;
   float* sc = reinterpret_cast<float*>(sm_raw);        // [guide_w] saliency (mid candidates first)
@@ -504,7 +519,8 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a) {
 // at all because every source row has left memory before the first store.  Costs the read of
 // the n rows that end up evicted.
 template <int PPR, int PIECES, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a) {
+__global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a0, const EvictLayers ly) {
+  const EvictArgs a = layer_args(a0, ly);
   extern __shared__ int sm_raw[];
   const int m = a.mid_n, w = a.guide_w;
   float* sc = reinterpret_cast<float*>(sm_raw);        // [guide_w] saliency (mid candidates first)
@@ -635,43 +651,81 @@ unsigned grid_for(size_t n) {
 
 }  // namespace
 
+// Launch geometry of the end-of-line kernels for one configuration.
+struct EvictShape {
+  bool fast4, fast8, queue_in_lds, small;
+  int threads;
+  size_t dyn;
+};
 template <int PPR>
-hipError_t launch_evict_t(const EvictArgs& a0, hipStream_t s) {
-  EvictArgs a = a0;
+EvictShape evict_shape(const EvictArgs& a) {
+  EvictShape sh;
   const size_t fixed = (size_t)a.guide_w + 2 * (size_t)a.mid_n;
-  a.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
-  const dim3 grid((unsigned)a.n_pairs);
+  sh.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
   const int64_t pieces = (int64_t)(a.mid_n + a.n_tail) * PPR;
   // Measured on the five workloads: with at least two pairs per compute unit the tiled
   // kernel wins (it never reads the evicted rows); with fewer pairs than that and more than
   // one tile of rows (Lumina: 256 pairs, 245 rows of 256 B) the register-resident kernel with
   // 16 wavefronts per pair is 1.5x faster.
-  const bool fast4 = a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4;
-  const bool fast8 = a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8;
-  const int threads = fast4 || fast8 ? 1024 : kBlock;
-  const size_t dyn = (fixed + saliency_lds_words(a, threads, fixed, !fast8)) * sizeof(int);
-  hipError_t e;
-  if (fast4) {
-    if ((e = allow_lds(evict_fast_kernel<PPR, 4, 1024>, dyn)) != hipSuccess) return e;
-    hipLaunchKernelGGL((evict_fast_kernel<PPR, 4, 1024>), grid, dim3(1024), dyn, s, a);
-  } else if (fast8) {
-    if ((e = allow_lds(evict_fast_kernel<PPR, 8, 1024>, dyn)) != hipSuccess) return e;
-    hipLaunchKernelGGL((evict_fast_kernel<PPR, 8, 1024>), grid, dim3(1024), dyn, s, a);
+  sh.fast4 = a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4;
+  sh.fast8 = a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8;
+  sh.threads = sh.fast4 || sh.fast8 ? 1024 : kBlock;
+  sh.small = !sh.fast8 && saliency_is_small(a, sh.threads);
+  sh.dyn = (fixed + saliency_lds_words(a, sh.threads, fixed, !sh.fast8)) * sizeof(int);
+  return sh;
+}
+
+template <int PPR>
+hipError_t launch_evict_t(const EvictArgs& a0, const EvictLayers* ly0, hipStream_t s) {
+  EvictArgs a = a0;
+  EvictLayers ly;
+  if (ly0) {
+    ly = *ly0;
   } else {
-    if ((e = allow_lds(evict_kernel<PPR>, dyn)) != hipSuccess) return e;
-    hipLaunchKernelGGL((evict_kernel<PPR>), grid, dim3(kBlock), dyn, s, a);
+    ly = EvictLayers{};
+    ly.count = 1;
+    ly.kc[0] = a.kc;
+    ly.vc[0] = a.vc;
+  }
+  if (ly.count < 1 || ly.count > kMaxEvictLayers) return hipErrorInvalidValue;
+  const EvictShape sh = evict_shape<PPR>(a);
+  a.queue_in_lds = sh.queue_in_lds;
+  const dim3 grid((unsigned)a.n_pairs, (unsigned)ly.count);
+  hipError_t e;
+  if (sh.fast4) {
+    if ((e = allow_lds(evict_fast_kernel<PPR, 4, 1024>, sh.dyn)) != hipSuccess) return e;
+    hipLaunchKernelGGL((evict_fast_kernel<PPR, 4, 1024>), grid, dim3(1024), sh.dyn, s, a, ly);
+  } else if (sh.fast8) {
+    if ((e = allow_lds(evict_fast_kernel<PPR, 8, 1024>, sh.dyn)) != hipSuccess) return e;
+    hipLaunchKernelGGL((evict_fast_kernel<PPR, 8, 1024>), grid, dim3(1024), sh.dyn, s, a, ly);
+  } else {
+    if ((e = allow_lds(evict_kernel<PPR>, sh.dyn)) != hipSuccess) return e;
+    hipLaunchKernelGGL((evict_kernel<PPR>), grid, dim3(kBlock), sh.dyn, s, a, ly);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s) {
+hipError_t launch_evict(const EvictArgs& a, const EvictLayers* ly, int dtype, int head_dim, hipStream_t s) {
   const int row_bytes = head_dim * (dtype == 1 ? 2 : 4);
   switch (row_bytes / 16) {
-    case 8: return launch_evict_t<8>(a, s);
-    case 16: return launch_evict_t<16>(a, s);
-    case 32: return launch_evict_t<32>(a, s);
+    case 8: return launch_evict_t<8>(a, ly, s);
+    case 16: return launch_evict_t<16>(a, ly, s);
+    case 32: return launch_evict_t<32>(a, ly, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+bool evict_layers_may_share_launch(const EvictArgs& a, int dtype, int head_dim) {
+  if (!a.qq) return true;   // a queue of logits has its own rows per layer
+  const int row_bytes = head_dim * (dtype == 1 ? 2 : 4);
+  EvictShape sh;
+  switch (row_bytes / 16) {
+    case 8: sh = evict_shape<8>(a); break;
+    case 16: sh = evict_shape<16>(a); break;
+    case 32: sh = evict_shape<32>(a); break;
+    default: return false;
+  }
+  return sh.small || sh.queue_in_lds;   // the logits never leave LDS / registers
 }
 
 template <int PPR>

@@ -81,11 +81,27 @@ struct EvictArgs {
   int32_t n_tail;    // rows behind mid that slide down (r lines)
 };
 
+// The layers one end-of-line launch covers (grid.y): layer i of the launch uses kc[i], vc[i] and
+// the scratch parts of EvictArgs advanced by i strides.  All of them are in the same state.
+constexpr int kMaxEvictLayers = 48;
+struct EvictLayers {
+  int32_t count;
+  int64_t guide_stride;  // floats
+  int64_t qq_stride;     // bytes
+  int64_t pos_stride;    // int32 entries
+  int64_t acc_stride;    // floats
+  void* kc[kMaxEvictLayers];
+  void* vc[kMaxEvictLayers];
+};
+
 hipError_t launch_decode(const DecodeArgs& a, int dtype, int head_dim, hipStream_t s);
 int decode_rows_per_group(int dtype, int head_dim);   // keys one wave-wide load covers
 int decode_max_waves(int depth);                      // wavefronts per workgroup at that depth
 int decode_depth_for(int groups_per_wave);            // smallest instantiated depth >= the argument, 0 if none
-hipError_t launch_evict(const EvictArgs& a, int dtype, int head_dim, hipStream_t s);
+// `ly` may be null (one layer: a.kc, a.vc).  False from evict_layers_may_share_launch means the
+// launch would route every layer's logits through the one shared global scratch row set.
+hipError_t launch_evict(const EvictArgs& a, const EvictLayers* ly, int dtype, int head_dim, hipStream_t s);
+bool evict_layers_may_share_launch(const EvictArgs& a, int dtype, int head_dim);
 // out[P, mid_n] = saliency of the mid candidates from the queue rows so far (Eq. 9; in mode 2
 // the accumulated attention including the rows so far).
 hipError_t launch_saliency(const EvictArgs& a, int dtype, int head_dim, float* out, hipStream_t s);

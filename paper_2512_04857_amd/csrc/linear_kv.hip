@@ -444,7 +444,7 @@ int end_of_line_evict(linear_kv_t* kv, int32_t layer, void* stream) {
     fill_line_args(*kv, layer, c.line_len, &a);
     hipError_t e = hipSuccess;
     if (evicts)
-      e = linear::launch_evict(a, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
+      e = linear::launch_evict(a, nullptr, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
     else if (a.n_cols > 0)   // accumulated attention: fold the line's queue into the accumulators
       e = linear::launch_saliency(a, c.dtype, c.head_dim, nullptr, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
@@ -475,9 +475,52 @@ int decode_step_rope_layers(linear_kv_t* kv, int32_t first_layer, int32_t count,
 int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, int32_t count, void* stream) {
   if (!kv) return LINEAR_ENULL;
   if (count < 0 || first_layer < 0 || (int64_t)first_layer + count > kv->cfg.n_layers) return LINEAR_EINVAL;
-  for (int32_t i = 0; i < count; ++i) {
-    const int rc = end_of_line_evict(kv, first_layer + i, stream);
-    if (rc != LINEAR_OK) return rc;
+  const linear_cfg_t& c = kv->cfg;
+  const Derived& d = kv->d;
+  // Layers in the same state that end an evicting line share launches (their evictions do not
+  // depend on one another): one launch per group of layers instead of one per layer.
+  bool together = count > 1;
+  for (int32_t i = 0; i < count && together; ++i) {
+    const LayerState& a = kv->layer[first_layer + i];
+    const LayerState& b = kv->layer[first_layer];
+    together = a.in_line == c.line_len && a.lines_done == b.lines_done && a.visual_len == b.visual_len &&
+               a.mapped == b.mapped;
+  }
+  if (together) together = line_evicts(*kv, kv->layer[first_layer].lines_done + 1);
+  linear::EvictArgs a;
+  if (together) {
+    fill_line_args(*kv, first_layer, c.line_len, &a);
+    together = linear::evict_layers_may_share_launch(a, c.dtype, c.head_dim);
+  }
+  if (!together) {
+    for (int32_t i = 0; i < count; ++i) {
+      const int rc = end_of_line_evict(kv, first_layer + i, stream);
+      if (rc != LINEAR_OK) return rc;
+    }
+    return LINEAR_OK;
+  }
+  for (int32_t l0 = 0; l0 < count; l0 += linear::kMaxEvictLayers) {
+    const int32_t m = std::min<int32_t>(linear::kMaxEvictLayers, count - l0);
+    fill_line_args(*kv, first_layer + l0, c.line_len, &a);
+    linear::EvictLayers ly = {};
+    ly.count = m;
+    ly.guide_stride = (int64_t)d.guide_layer;
+    ly.qq_stride = (int64_t)d.qq_layer;
+    ly.pos_stride = (int64_t)d.pos_layer;
+    ly.acc_stride = (int64_t)d.acc_layer;
+    for (int32_t i = 0; i < m; ++i) {
+      ly.kc[i] = kv->k_cache[first_layer + l0 + i];
+      ly.vc[i] = kv->v_cache[first_layer + l0 + i];
+    }
+    const hipError_t e = linear::launch_evict(a, &ly, c.dtype, c.head_dim, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);   // layers of earlier groups have been enqueued and advanced
+    for (int32_t i = 0; i < m; ++i) {
+      LayerState& ls = kv->layer[first_layer + l0 + i];
+      ls.visual_len -= c.line_len;
+      ls.mapped = d.mid_n - c.line_len;
+      ls.in_line = 0;
+      ls.lines_done += 1;
+    }
   }
   return LINEAR_OK;
 }
