@@ -658,7 +658,7 @@ struct EvictShape {
   size_t dyn;
 };
 template <int PPR>
-EvictShape evict_shape(const EvictArgs& a) {
+EvictShape evict_shape(const EvictArgs& a, int n_layers = 1) {
   EvictShape sh;
   const size_t fixed = (size_t)a.guide_w + 2 * (size_t)a.mid_n;
   sh.queue_in_lds = queue_fits_lds(a.n_rows, a.guide_w, fixed);
@@ -667,8 +667,14 @@ EvictShape evict_shape(const EvictArgs& a) {
   // kernel wins (it never reads the evicted rows); with fewer pairs than that and more than
   // one tile of rows (Lumina: 256 pairs, 245 rows of 256 B) the register-resident kernel with
   // 16 wavefronts per pair is 1.5x faster.
-  sh.fast4 = a.n_pairs <= 256 && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4;
-  sh.fast8 = a.n_pairs <= 256 && pieces > 1024 * 4 && pieces <= 1024 * 8;
+  // Across the layers of a shared launch the same holds per workgroup count -- unless the
+  // line's logits take so much LDS that fewer than three 4-wavefront workgroups fit a compute
+  // unit (Lumina-mGPT-1024: 102 KB), where 16 wavefronts per workgroup keep it busy.
+  const int64_t groups = (int64_t)a.n_pairs * n_layers;   // workgroups of the launch
+  const size_t dyn_tiled = (fixed + saliency_lds_words(a, kBlock, fixed)) * sizeof(int);
+  const bool few = groups <= 256 || dyn_tiled > 160 * 1024 / 3;
+  sh.fast4 = few && pieces > kBlock * kPiecesPerThread && pieces <= 1024 * 4;
+  sh.fast8 = few && pieces > 1024 * 4 && pieces <= 1024 * 8;
   sh.threads = sh.fast4 || sh.fast8 ? 1024 : kBlock;
   sh.small = !sh.fast8 && saliency_is_small(a, sh.threads);
   sh.dyn = (fixed + saliency_lds_words(a, sh.threads, fixed, !sh.fast8)) * sizeof(int);
@@ -688,7 +694,7 @@ hipError_t launch_evict_t(const EvictArgs& a0, const EvictLayers* ly0, hipStream
     ly.vc[0] = a.vc;
   }
   if (ly.count < 1 || ly.count > kMaxEvictLayers) return hipErrorInvalidValue;
-  const EvictShape sh = evict_shape<PPR>(a);
+  const EvictShape sh = evict_shape<PPR>(a, ly.count);
   a.queue_in_lds = sh.queue_in_lds;
   const dim3 grid((unsigned)a.n_pairs, (unsigned)ly.count);
   hipError_t e;
@@ -715,14 +721,14 @@ hipError_t launch_evict(const EvictArgs& a, const EvictLayers* ly, int dtype, in
   }
 }
 
-bool evict_layers_may_share_launch(const EvictArgs& a, int dtype, int head_dim) {
+bool evict_layers_may_share_launch(const EvictArgs& a, int n_layers, int dtype, int head_dim) {
   if (!a.qq) return true;   // a queue of logits has its own rows per layer
   const int row_bytes = head_dim * (dtype == 1 ? 2 : 4);
   EvictShape sh;
   switch (row_bytes / 16) {
-    case 8: sh = evict_shape<8>(a); break;
-    case 16: sh = evict_shape<16>(a); break;
-    case 32: sh = evict_shape<32>(a); break;
+    case 8: sh = evict_shape<8>(a, n_layers); break;
+    case 16: sh = evict_shape<16>(a, n_layers); break;
+    case 32: sh = evict_shape<32>(a, n_layers); break;
     default: return false;
   }
   return sh.small || sh.queue_in_lds;   // the logits never leave LDS / registers

@@ -101,7 +101,7 @@ int decode_depth_for(int groups_per_wave);            // smallest instantiated d
 // `ly` may be null (one layer: a.kc, a.vc).  False from evict_layers_may_share_launch means the
 // launch would route every layer's logits through the one shared global scratch row set.
 hipError_t launch_evict(const EvictArgs& a, const EvictLayers* ly, int dtype, int head_dim, hipStream_t s);
-bool evict_layers_may_share_launch(const EvictArgs& a, int dtype, int head_dim);
+bool evict_layers_may_share_launch(const EvictArgs& a, int n_layers, int dtype, int head_dim);
 // out[P, mid_n] = saliency of the mid candidates from the queue rows so far (Eq. 9; in mode 2
 // the accumulated attention including the rows so far).
 hipError_t launch_saliency(const EvictArgs& a, int dtype, int head_dim, float* out, hipStream_t s);

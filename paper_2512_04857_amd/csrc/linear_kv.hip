@@ -490,7 +490,8 @@ int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, int32_t count
   linear::EvictArgs a;
   if (together) {
     fill_line_args(*kv, first_layer, c.line_len, &a);
-    together = linear::evict_layers_may_share_launch(a, c.dtype, c.head_dim);
+    together = linear::evict_layers_may_share_launch(a, std::min<int32_t>(count, linear::kMaxEvictLayers),
+                                                     c.dtype, c.head_dim);
   }
   if (!together) {
     for (int32_t i = 0; i < count; ++i) {
