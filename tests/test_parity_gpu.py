@@ -426,3 +426,13 @@ def test_full_size_properties_every_pair(w):
             assert torch.equal(kg[..., :C, :], kc[l]) and torch.equal(vg[..., :C, :], vc[l])
     torch.cuda.synchronize()
     cache.close()
+
+
+def test_more_layers_than_one_end_of_line_launch_covers():
+    """50 layers: end_of_line_evict_layers needs two launches (48 + 2 layers); the oracle follows
+    layers on both sides of the boundary."""
+    w = synth.Workload("many-layers", 50, 1, 2, 64, 3, 4, 7, 12, 4, 1, "bf16", 34)
+    sl = sampled_slices(w, [0, 47, 48, 49], [0], [0, 1])
+    rep = run_parity(w, sl, layers_call=True)
+    say(f"{w.name}: {rep}")
+    assert rep.steps == w.n_visual and rep.evictions == (7 - 3 - 1 + 1) * len(sl)
