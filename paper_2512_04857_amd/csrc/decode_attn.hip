@@ -163,13 +163,15 @@ __device__ __forceinline__ uint4 rotate_row(const uint4& r, const float (&cc)[EP
   return make_uint4(ow[0], ow[1], ow[2], ow[3]);
 }
 
-template <int U>
+template <int U, bool ROPE>
 struct MaxWaves {   // waves per workgroup the register budget of a U-deep wavefront allows
-  static constexpr int value = U <= 8 ? 16 : (U <= 12 ? 12 : 8);
+  // deeper than 8: three per SIMD (170 registers each); the deepest one with the rotary
+  // embedding needs a few more than that
+  static constexpr int value = U <= 8 ? 16 : (ROPE && U > 14 ? 8 : 12);
 };
 
 template <bool BF16, int D, int U, bool ROPE>
-__global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_kernel(const DecodeArgs a) {
   using E = Elems<BF16>;
   constexpr int EPL = E::kPerLane;   // elements per lane
   constexpr int LPR = D / EPL;       // lanes per key row
@@ -302,7 +304,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(co
     const int worker = wave * RPW + sub;
     float4* dst = reinterpret_cast<float4*>(sm_o + worker * D + seg * EPL);
     dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-    if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+    if constexpr (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
     if (seg == 0) sm_l[worker] = l;
     if (lane == 0) sm_m[wave] = m_wave;
   }
@@ -414,7 +416,7 @@ int decode_rows_per_group(int dtype, int head_dim) {
   return 64 / lanes_per_row;
 }
 
-int decode_max_waves(int depth) { return depth <= 8 ? 16 : (depth <= 12 ? 12 : 8); }
+int decode_max_waves(int depth, bool rope) { return depth <= 8 ? 16 : (rope && depth > 14 ? 8 : 12); }
 
 int decode_depth_for(int groups_per_wave) {
   static const int kDepths[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};

@@ -119,7 +119,7 @@ def test_launch_shape_covers_every_step(name, full, guide_queue):
             assert p["n_split"] * p["keys_per_workgroup"] >= keys
             assert p["n_split"] == 1 or (p["n_split"] - 1) * p["keys_per_workgroup"] < keys
             assert p["depth"] in DEPTHS
-            assert 1 <= p["n_waves"] <= (16 if p["depth"] <= 8 else 12 if p["depth"] <= 12 else 8)
+            assert 1 <= p["n_waves"] <= (16 if p["depth"] <= 8 else 12)
             assert p["n_waves"] * p["depth"] * rpg >= p["keys_per_workgroup"]
             assert 0 <= p["new_wave"] < p["n_waves"]
             if ns:
