@@ -9,8 +9,12 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblinear_kv.so")
 SOURCES = ["linear_kv.hip", "decode_attn.hip", "evict.hip"]
 # -packed-fp32-ops off: the compiler must not form v_pk_*_f32 from the float code.
+# amdgpu-kernarg-preload-count: the leading scalar kernel arguments (the decode kernel's pointers
+# and packed sizes) arrive in SGPRs with the wavefront instead of through a scalar load; measured
+# 0.2-0.4 us per decode launch.  Code objects keep a prologue for firmware without the feature.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-result"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm",
+         "-amdgpu-kernarg-preload-count=14", "-Wall", "-Wno-unused-result"]
 
 
 def hipcc() -> str:

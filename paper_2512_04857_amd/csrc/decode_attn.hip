@@ -170,15 +170,25 @@ struct MaxWaves {   // waves per workgroup the register budget of a U-deep wavef
   static constexpr int value = U <= 8 ? 16 : (ROPE && U > 14 ? 8 : 12);
 };
 
+// The first arguments are the ones the loads depend on, as scalars at the front of the kernel
+// argument segment: with kernel-argument preloading (build flag) they arrive in SGPRs with the
+// wavefront, so the first load does not wait for a scalar fetch of the arguments.  `t_nw` =
+// keys visible to the query | wavefronts per workgroup << 24; `tmax_gps` = row pitch of the
+// caches | row groups per workgroup << 21.  The rest is read from `a`, after the loads are out.
 template <bool BF16, int D, int U, bool ROPE>
-__global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_kernel(
+    const void* __restrict__ q_in, void* __restrict__ kc_in, void* __restrict__ vc_in,
+    const void* __restrict__ k_in, const void* __restrict__ v_in, const uint32_t t_nw,
+    const uint32_t tmax_gps, const DecodeArgs a) {
   using E = Elems<BF16>;
   constexpr int EPL = E::kPerLane;   // elements per lane
   constexpr int LPR = D / EPL;       // lanes per key row
   constexpr int RPW = 64 / LPR;      // rows per wave-wide load = softmax workers per wavefront
 
   extern __shared__ float smem[];
-  const int nw = blockDim.x >> 6;
+  const int nw = (int)(t_nw >> 24);
+  const int t = (int)(t_nw & 0xffffffu), t_max = (int)(tmax_gps & 0x1fffffu);
+  const int rows_per_split = (int)(tmax_gps >> 21) * RPW;
   const int n_workers = nw * RPW;
   float* sm_o = smem;                        // [n_workers][D] numerators, scaled to the wave's max
   float* sm_l = sm_o + n_workers * D;        // [n_workers]    sums, likewise
@@ -189,23 +199,19 @@ __global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_k
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int seg = lane % LPR, sub = lane / LPR;
   const int pair = blockIdx.x, split = blockIdx.y;
-  const int r0 = split * a.rows_per_split;               // cached rows [r0, r0 + n_rows)
-  const int n_rows = min(a.t - 1, r0 + a.rows_per_split) - r0;
-  const bool scoring = a.mid_n > 0;
-  // The appended token is counted by sub-group 0 of one wavefront of the last split (the
-  // host picks the one with the fewest row groups).
-  const bool owner = split == a.n_split - 1 && wave == a.new_wave && sub == 0;
+  const int r0 = split * rows_per_split;                 // cached rows [r0, r0 + n_rows)
+  const int n_rows = min(t - 1, r0 + rows_per_split) - r0;
 
   // ---- loads: straight-line, so that every later wait counts exactly the loads behind it.
   // Addresses are a uniform base plus a 32-bit lane offset.  Row groups beyond the end
   // re-read the last row (served by the caches) and are masked.
   constexpr unsigned kRowBytes = LPR * 16;
-  const char* kbase = static_cast<const char*>(a.kc) + ((size_t)pair * a.t_max + r0) * kRowBytes;
-  const char* vbase = static_cast<const char*>(a.vc) + ((size_t)pair * a.t_max + r0) * kRowBytes;
+  const char* kbase = static_cast<const char*>(kc_in) + ((size_t)pair * t_max + r0) * kRowBytes;
+  const char* vbase = static_cast<const char*>(vc_in) + ((size_t)pair * t_max + r0) * kRowBytes;
   const unsigned in_off = (unsigned)seg * 16u;
-  uint4 qr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.q) + (size_t)pair * kRowBytes + in_off);
-  uint4 knr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.k_new) + (size_t)pair * kRowBytes + in_off);
-  const uint4 vnr = *reinterpret_cast<const uint4*>(static_cast<const char*>(a.v_new) + (size_t)pair * kRowBytes + in_off);
+  uint4 qr = *reinterpret_cast<const uint4*>(static_cast<const char*>(q_in) + (size_t)pair * kRowBytes + in_off);
+  uint4 knr = *reinterpret_cast<const uint4*>(static_cast<const char*>(k_in) + (size_t)pair * kRowBytes + in_off);
+  const uint4 vnr = *reinterpret_cast<const uint4*>(static_cast<const char*>(v_in) + (size_t)pair * kRowBytes + in_off);
   float rc[EPL], rs[EPL];   // this lane's rotary cosines and sines: requested ahead of the cache rows
   if (ROPE) {
     const float* cs = a.cos_sin + (seg * EPL) % (D / 2);
@@ -233,6 +239,10 @@ __global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_k
   // hold back the rest of the requests for a full memory round trip.
   __builtin_amdgcn_sched_barrier(0);
 
+  const bool scoring = a.mid_n > 0;
+  // The appended token is counted by sub-group 0 of one wavefront of the last split (the
+  // host picks the one with the fewest row groups).
+  const bool owner = split == a.n_split - 1 && wave == a.new_wave && sub == 0;
   if (ROPE) {
     // q and k of the new token arrive unrotated: every lane rotates its piece of both (all
     // wavefronts need q; k is only used by the lane group that appends it, but rotating it
@@ -245,9 +255,9 @@ __global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_k
   // been acknowledged, so a store issued near the end adds its whole latency to the step.
   if (owner) {
     // Eq. 4: the new pair becomes row T-1 of the cache.
-    const size_t dst = ((size_t)pair * a.t_max + (a.t - 1)) * LPR + seg;
-    store_nt(&reinterpret_cast<uint4*>(a.kc)[dst], knr);
-    store_nt(&reinterpret_cast<uint4*>(a.vc)[dst], vnr);
+    const size_t dst = ((size_t)pair * t_max + (t - 1)) * LPR + seg;
+    store_nt(&reinterpret_cast<uint4*>(kc_in)[dst], knr);
+    store_nt(&reinterpret_cast<uint4*>(vc_in)[dst], vnr);
     // Eq. 8 as printed: the query joins the line's guide queue (one aligned row)
     if (a.qq) store_nt(reinterpret_cast<uint4*>(static_cast<char*>(a.qq) + (size_t)pair * a.qq_pitch) + seg, qr);
   }
@@ -277,7 +287,7 @@ __global__ __launch_bounds__((64 * MaxWaves<U, ROPE>::value)) void decode_attn_k
       }
     }
     // accumulated attention also scores the appended token (row T-1) under its own query
-    if (a.stage_new && owner && seg == 0 && a.t - 1 >= a.mid_lo) sm_mid[a.t - 1 - a.mid_lo] = s_new * c;
+    if (a.stage_new && owner && seg == 0 && t - 1 >= a.mid_lo) sm_mid[t - 1 - a.mid_lo] = s_new * c;
   }
   // ---- probabilities relative to the worker's own maximum, and its numerator
   const float m_ref = m > ninf() ? m : 0.f;
@@ -381,8 +391,14 @@ hipError_t launch_main(const DecodeArgs& a, hipStream_t s) {
   const int workers = a.n_waves * RPW;
   const size_t dyn = ((size_t)workers * (D + 1) + a.n_waves + (size_t)a.mid_n) * sizeof(float);
   const dim3 grid((unsigned)a.n_pairs, (unsigned)a.n_split), block(64u * (unsigned)a.n_waves);
-  if (a.cos_sin) hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U, true>), grid, block, dyn, s, a);
-  else hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U, false>), grid, block, dyn, s, a);
+  const uint32_t t_nw = (uint32_t)a.t | ((uint32_t)a.n_waves << 24);
+  const uint32_t tmax_gps = (uint32_t)a.t_max | ((uint32_t)(a.rows_per_split / RPW) << 21);
+  if (a.cos_sin)
+    hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U, true>), grid, block, dyn, s, a.q, a.kc, a.vc, a.k_new,
+                       a.v_new, t_nw, tmax_gps, a);
+  else
+    hipLaunchKernelGGL((decode_attn_kernel<BF16, D, U, false>), grid, block, dyn, s, a.q, a.kc, a.vc, a.k_new,
+                       a.v_new, t_nw, tmax_gps, a);
   return hipGetLastError();
 }
 
