@@ -96,7 +96,7 @@ struct EvictLayers {
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, int head_dim, hipStream_t s);
 int decode_rows_per_group(int dtype, int head_dim);   // keys one wave-wide load covers
-int decode_max_waves(int depth, bool rope);           // wavefronts per workgroup at that depth
+int decode_max_waves(int depth);                      // wavefronts per workgroup at that depth
 int decode_depth_for(int groups_per_wave);            // smallest instantiated depth >= the argument, 0 if none
 // `ly` may be null (one layer: a.kc, a.vc).  False from evict_layers_may_share_launch means the
 // launch would route every layer's logits through the one shared global scratch row set.

@@ -141,8 +141,8 @@ struct Plan {
   int n_split, rows_per_split, n_waves, depth, new_wave;
 };
 
-bool make_plan(int dtype, int head_dim, int pairs, bool stages_logits, bool rope, int target,
-               int force_split, int cached_rows, Plan* p) {
+bool make_plan(int dtype, int head_dim, int pairs, bool stages_logits, int target, int force_split,
+               int cached_rows, Plan* p) {
   const int rpg = linear::decode_rows_per_group(dtype, head_dim);
   const int groups = ceil_div(cached_rows, rpg);
   int n_split = force_split;
@@ -188,7 +188,7 @@ bool make_plan(int dtype, int head_dim, int pairs, bool stages_logits, bool rope
     const int cand = k < 17 - nw ? nw + k : nw - (k - (16 - nw));
     if (cand < 1 || cand > 16) continue;
     const int depth = linear::decode_depth_for(ceil_div(gps, cand));
-    if (depth == 0 || cand > linear::decode_max_waves(depth, rope)) continue;
+    if (depth == 0 || cand > linear::decode_max_waves(depth)) continue;
     p->n_split = n_split;
     p->rows_per_split = gps * rpg;
     p->depth = depth;
@@ -362,8 +362,8 @@ int decode_step_impl(linear_kv_t* kv, int32_t layer, const void* q, const void* 
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
   Plan plan;
-  if (!make_plan(c.dtype, c.head_dim, d.pairs, d.compresses && !d.queries, cos_sin != nullptr,
-                 kv->groups_per_wave, kv->force_split, a.t - 1, &plan))
+  if (!make_plan(c.dtype, c.head_dim, d.pairs, d.compresses && !d.queries, kv->groups_per_wave,
+                 kv->force_split, a.t - 1, &plan))
     return LINEAR_EINVAL;
   a.n_split = plan.n_split;
   a.rows_per_split = plan.rows_per_split;
@@ -597,8 +597,8 @@ int linear_plan_shape(const linear_cfg_t* cfg, int32_t cached_keys, int32_t grou
       n_split < 0 || n_split > linear::kMaxSplit)
     return LINEAR_EINVAL;
   Plan p;
-  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, d.compresses && !d.queries, false, groups_per_wave,
-                 n_split, cached_keys, &p))
+  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, d.compresses && !d.queries, groups_per_wave, n_split,
+                 cached_keys, &p))
     return LINEAR_EINVAL;
   shape[0] = p.n_split;
   shape[1] = p.rows_per_split;
