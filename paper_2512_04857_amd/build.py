@@ -12,9 +12,12 @@ SOURCES = ["linear_kv.hip", "decode_attn.hip", "evict.hip"]
 # amdgpu-kernarg-preload-count: the leading scalar kernel arguments (the decode kernel's pointers
 # and packed sizes) arrive in SGPRs with the wavefront instead of through a scalar load; measured
 # 0.2-0.4 us per decode launch.  Code objects keep a prologue for firmware without the feature.
+# LINEAR_KERNARG_PRELOAD=0 in the environment builds without it (same results; rocprofv3's
+# counter collection crashed in its own dispatch interception with the preloading code objects,
+# so the counter profiles are taken from such a build).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm",
-         "-amdgpu-kernarg-preload-count=14", "-Wall", "-Wno-unused-result"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-result"]
+PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=14"]
 
 
 def hipcc() -> str:
@@ -22,7 +25,8 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = False, extra=()) -> str:
-    cmd = [hipcc(), *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    preload = [] if os.environ.get("LINEAR_KERNARG_PRELOAD", "1") == "0" else PRELOAD
+    cmd = [hipcc(), *FLAGS, *preload, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
