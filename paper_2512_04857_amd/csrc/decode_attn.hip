@@ -17,12 +17,16 @@
 //   * the new token is one extra row taken from the inputs; one wavefront counts it and
 //     writes it to the cache (Eq. 4); its original position is implied by its row (only the
 //     survivors of evictions need a position map, and the end-of-line kernel keeps it);
-//   * on lines that end in an eviction the logits of the mid keys are appended to the line's
-//     guide queue (Eq. 8), staged through LDS so that they leave as one coalesced store; the
-//     softmax rows of Eq. 9 are evaluated once per line by the eviction kernel, so a decode
-//     step carries no reduction for them;
-//   * stores are few and early (the new row goes out right after the loads): a kernel this
-//     short pays for every store instruction and for the full latency of a late one;
+//   * on lines that end in an eviction the query joins the line's guide queue (Eq. 8): either
+//     the query itself, stored with the new row, or -- for the modes that score decode-time
+//     probabilities -- its logits on the scored keys, staged through LDS so that they leave as
+//     one coalesced store; the softmax rows of Eq. 9 are evaluated once per line by the
+//     end-of-line kernel, so a decode step carries no reduction for them;
+//   * stores are few, early (the new row goes out right after the loads) and cover whole
+//     aligned 128-byte lines: a kernel this short pays for every store instruction, for the
+//     full latency of a late one and for the read-modify-write of a line written in part;
+//   * what the loads need arrives as leading scalar kernel arguments (preloaded into SGPRs
+//     where the firmware supports it), the rest of the arguments is fetched behind the loads;
 //   * a pair whose keys fit one workgroup (up to 144 row groups) is a single launch with
 //     no inter-workgroup traffic; longer ones are split over workgroups and merged by
 //     a second, tiny kernel (a kernel boundary is cheaper here than device-scope fences).
