@@ -436,3 +436,55 @@ def test_more_layers_than_one_end_of_line_launch_covers():
     rep = run_parity(w, sl, layers_call=True)
     say(f"{w.name}: {rep}")
     assert rep.steps == w.n_visual and rep.evictions == (7 - 3 - 1 + 1) * len(sl)
+
+
+def test_decode_steps_replayed_from_a_hip_graph():
+    """The decode steps of a line captured into a HIP graph (the launch sequence is static: cache
+    lengths do not depend on the data) and replayed give, on every replay, what the same calls
+    give when enqueued directly; eager work and synchronisations sit between the replays.  The
+    library enqueues kernels only (no memset, no allocation), so every call can be captured."""
+    w = MID_SPLIT
+    dev = "cuda:0"
+    kc, vc = synth.cond_kv(w, dev)
+    n, L = w.line_len, w.n_layers
+    lines = w.budget // n + 1                                     # up to and including two evicting lines
+    qs, ks, vs = synth.image_qkv(w, dev, steps=lines * n)
+    stride = qs[0, 0].numel() * qs.element_size()
+
+    def run(use_graph):
+        cache = binding.LineARCache(binding.cfg_from_workload(w), dev)
+        cache.start_image(kc, vc)
+        outs = torch.zeros((lines * n, L, w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=dev)
+        ostride = outs[0, 0].numel() * 4
+        for line in range(lines):
+            def steps(stream):
+                for s in range(line * n, (line + 1) * n):
+                    binding.decode_step_layers(cache.handle, 0, L, qs[s].data_ptr(), ks[s].data_ptr(),
+                                               vs[s].data_ptr(), outs[s].data_ptr(), stride, ostride, stream)
+            if use_graph:
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    steps(torch.cuda.current_stream().cuda_stream)
+                first = None
+                for _ in range(3):
+                    outs[line * n:(line + 1) * n].zero_()           # eager work between the replays
+                    g.replay()
+                    torch.cuda.synchronize()
+                    got = outs[line * n:(line + 1) * n].clone()
+                    assert first is None or torch.equal(got, first)
+                    first = got
+            else:
+                steps(cache.stream())
+            binding.end_of_line_evict_layers(cache.handle, 0, L, cache.stream())
+        torch.cuda.synchronize()
+        kept = [tuple(t.clone() for t in cache.gather(l)) for l in range(L)]
+        cache.close()
+        return outs, kept
+
+    eager_out, eager_kept = run(False)
+    graph_out, graph_kept = run(True)
+    assert torch.equal(graph_out, eager_out)
+    for a, b in zip(eager_kept, graph_kept):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
