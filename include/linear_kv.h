@@ -7,7 +7,7 @@
  *   - accumulation of the saliency of the mid tokens under the queries of the
  *     line being generated                                                (Eq. 8-9),
  *   - at the end of a raster line, BottomK selection of n mid tokens per
- *     head and the order-preserving compaction of K, V and the position map
+ *     head and the order-preserving compaction of K, V and the survivors' positions
  *                                                                        (Eq. 5-7, 10).
  * Symbols are the paper's (Sec. 3.1, 3.3): C, n (tokens per raster line, an
  * end-of-line token counts), h lines, N = h n, budget B (n divides B),
@@ -90,7 +90,8 @@ typedef struct {
  *   *cache_bytes_per_layer : bytes of EACH of the K and the V cache of one layer,
  *                            laid out [Bz, H, C + B, d] elem;
  *   *scratch_bytes         : bytes of the one scratch buffer shared by all layers
- *                            (saliency accumulators, position maps, split partials).
+ *                            (guide queues, survivor position maps, attention accumulators,
+ *                            split partials).
  * HOST pointers.  LINEAR_EINVAL if the configuration is not valid. */
 LINEAR_API int linear_workspace_bytes(const linear_cfg_t* cfg, size_t* cache_bytes_per_layer,
                            size_t* scratch_bytes);
