@@ -74,7 +74,7 @@ typedef struct {
                              2: accumulated attention (the paper's AttAcc ablation, Table 6):
                                 every token behind the anchor carries the sum of the
                                 decode-time probabilities it received from every query since
-                                it was appended, never reset; needs B - N_init <= 8192    */
+                                it was appended, never reset; needs B - N_init <= 7680    */
   int32_t guide_queue;    /* what the line's guide queue holds (Eq. 8):
                              LINEAR_QUEUE_QUERIES: the queries themselves, as Eq. 8 prints it;
                                 Eq. 9 is evaluated at the end of the line as the matrix

@@ -19,7 +19,9 @@ thread_local int g_last_hip_error = 0;
 
 using linear::kMaxMid;              // candidates the eviction kernel ranks in LDS
 constexpr int kMaxLine = 4096;      // guide queries whose row statistics it keeps in LDS
-constexpr int kMaxScored = 8192;    // scored slots per pair when attention is accumulated
+constexpr int kMaxScored = 7680;    // scored slots per pair when attention is accumulated: the decode step
+                                    // stages their logits in LDS next to up to 33 KB of softmax partials,
+                                    // within the 64 KiB every workgroup may use
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }

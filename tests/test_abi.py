@@ -58,12 +58,22 @@ def test_workspace_sizes():
     dict(guide_queue=2, score_mode=1), dict(guide_queue=2, score_mode=2),
     dict(scale=-1.0), dict(scale=float("nan")), dict(scale=float("inf")),
     dict(line_len=1, n_lines=100000, budget=50000, n_init=0),     # mid larger than the ranking limit
-    dict(score_mode=2, line_len=16, n_lines=1024, budget=8224, n_init=16, n_recent_lines=400),  # > 8192 scored slots
+    dict(score_mode=2, line_len=16, n_lines=1024, budget=7712, n_init=16, n_recent_lines=400),  # > 7680 scored slots
 ])
 def test_invalid_configurations_are_rejected(over):
     with pytest.raises(binding.LinearError) as e:
         binding.linear_workspace_bytes(good(**over))
     assert e.value.code == binding.LINEAR_EINVAL
+
+
+def test_largest_accumulated_attention_configuration_fits_the_decode_step():
+    """Score mode 2 stages B - N_init logits per step in LDS beside the softmax partials of up to
+    16 wavefronts: the largest accepted configuration keeps that within 64 KiB."""
+    cfg = good(score_mode=2, line_len=16, n_lines=1024, budget=7696, n_init=16, n_recent_lines=400)
+    binding.linear_workspace_bytes(cfg)                     # 7680 scored slots: accepted
+    workers_bytes = (16 * 8 * (64 + 1) + 16) * 4            # d = 64 bf16: 8 softmax workers per wavefront
+    assert workers_bytes + 7680 * 4 <= 64 * 1024
+    assert (16 * 4 * (128 + 1) + 16) * 4 + 7680 * 4 <= 64 * 1024   # d = 128
 
 
 def test_null_and_alignment_errors_without_touching_the_gpu():
