@@ -45,6 +45,7 @@ extern "C" {
 #define LINEAR_ENULL (-3)  /* required pointer is NULL                       */
 #define LINEAR_EALIGN (-4) /* device pointer not 16-byte aligned             */
 #define LINEAR_EHIP (-5)   /* a HIP call failed: see linear_last_hip_error() */
+#define LINEAR_ECAPACITY (-6) /* decode_step_static: the step needs more scratch than the library holds */
 
 #define LINEAR_F32 0
 #define LINEAR_BF16 1
@@ -176,6 +177,36 @@ LINEAR_API int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mi
  *                  the eviction schedule does not depend on the data). */
 LINEAR_API int kv_gather(linear_kv_t* kv, int32_t layer, void* k_out, void* v_out, int32_t* pos_out,
               int32_t* len_out, void* stream);
+
+/* decode_step for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * One stateless step on a cache the caller lays out itself: appends (k, v) as row
+ * `cached_keys` of every pair's K and V and writes out = Softmax(q K^T * scale) V over the
+ * cached_keys + 1 rows, exactly as decode_step does (same kernels).  When the keys of a pair
+ * are split over several workgroups, the split partials -- which decode_step keeps in the
+ * caller's workspace -- live in a device array inside the library: 4 MiB per GPU, held from
+ * the first call on that GPU until the process ends, its address looked up on that first call
+ * (make it, or a call of linear_static_scratch_bytes, outside graph capture).  The call
+ * allocates and frees nothing, on the host or on the device.
+ *   dtype, head_dim        : as in linear_cfg_t;
+ *   n_pairs                : (sequence, head) pairs, >= 1;
+ *   cached_keys            : rows already in the cache, >= 0;
+ *   cache_pitch            : rows between consecutive pairs in k_cache / v_cache, > cached_keys;
+ *   k_cache, v_cache       : DEVICE [n_pairs, cache_pitch, d] elem, rows [0, cached_keys) valid;
+ *   q, k, v                : DEVICE [n_pairs, d] elem;   out : DEVICE [n_pairs, d] float;
+ *   scale                  : logit scale, 0 selects 1/sqrt(d);
+ *   n_split                : workgroups per pair, 1..64, or 0 = chosen as decode_step chooses it.
+ * LINEAR_ECAPACITY when n_pairs * splits * (d + 2) floats exceed the 4 MiB (nothing enqueued);
+ * other errors as decode_step.  All calls on one GPU share that GPU's array, which keeps the
+ * last call's contents (nothing in it has to start at zero: every partial is written before it
+ * is read): calls that may overlap on one GPU, on different streams or threads, race. */
+LINEAR_API int decode_step_static(int32_t dtype, int32_t head_dim, int32_t n_pairs, int32_t cached_keys,
+                       int32_t cache_pitch, void* k_cache, void* v_cache, const void* q, const void* k,
+                       const void* v, float scale, int32_t n_split, void* out, void* stream);
+
+/* Capacity in bytes of the array decode_step_static keeps its partials in; also performs the
+ * one-time address lookup for the current device.  *bytes: HOST. */
+LINEAR_API int linear_static_scratch_bytes(size_t* bytes);
 
 /* Host-side queries (no device work). */
 LINEAR_API int kv_length(const linear_kv_t* kv, int32_t layer, int32_t* cached_tokens,

@@ -13,14 +13,14 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblinear_kv.so")
 
-LINEAR_OK, LINEAR_EINVAL, LINEAR_ESTATE, LINEAR_ENULL, LINEAR_EALIGN, LINEAR_EHIP = 0, -1, -2, -3, -4, -5
+LINEAR_OK, LINEAR_EINVAL, LINEAR_ESTATE, LINEAR_ENULL, LINEAR_EALIGN, LINEAR_EHIP, LINEAR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
 LINEAR_F32, LINEAR_BF16 = 0, 1
 LINEAR_QUEUE_AUTO, LINEAR_QUEUE_LOGITS, LINEAR_QUEUE_QUERIES = 0, 1, 2
 
 EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_layers",
            "decode_step_rope", "decode_step_rope_layers",
            "end_of_line_evict", "end_of_line_evict_layers", "kv_scores",
-           "kv_gather", "kv_length", "linear_set_tuning", "linear_plan_shape", "kv_free", "linear_strerror",
+           "decode_step_static", "linear_static_scratch_bytes", "kv_gather", "kv_length", "linear_set_tuning", "linear_plan_shape", "kv_free", "linear_strerror",
            "linear_last_hip_error")
 
 
@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
         L.linear_set_tuning.argtypes = [vp, i32, i32]
         L.linear_plan_shape.argtypes = [C.POINTER(LinearCfg), i32, i32, i32, C.POINTER(i32)]
         L.kv_free.argtypes = [vp]
+        L.decode_step_static.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, C.c_float, i32, vp, vp]
+        L.linear_static_scratch_bytes.argtypes = [C.POINTER(C.c_size_t)]
         L.linear_strerror.argtypes = [C.c_int]
         L.linear_strerror.restype = C.c_char_p
         L.linear_last_hip_error.argtypes = []
@@ -182,6 +184,21 @@ def linear_plan_shape(cfg: LinearCfg, cached_keys: int, groups_per_wave: int = 0
     out = (C.c_int32 * 6)()
     _check(lib().linear_plan_shape(C.byref(cfg), cached_keys, groups_per_wave, n_split, out), "linear_plan_shape")
     return dict(zip(("n_split", "keys_per_workgroup", "n_waves", "depth", "new_wave", "keys_per_group"), out))
+
+
+def decode_step_static(dtype: int, head_dim: int, n_pairs: int, cached_keys: int, cache_pitch: int, k_cache: int,
+                       v_cache: int, q: int, k: int, v: int, out: int, scale: float = 0.0, n_split: int = 0,
+                       stream: int = 0) -> None:
+    rc = lib().decode_step_static(dtype, head_dim, n_pairs, cached_keys, cache_pitch, k_cache, v_cache, q, k, v,
+                                  scale, n_split, out, stream)
+    if rc:
+        raise LinearError(rc, "decode_step_static")
+
+
+def linear_static_scratch_bytes() -> int:
+    n = C.c_size_t()
+    _check(lib().linear_static_scratch_bytes(C.byref(n)), "linear_static_scratch_bytes")
+    return n.value
 
 
 def kv_free(kv: int) -> None:

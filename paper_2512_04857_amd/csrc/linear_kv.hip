@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -118,6 +119,41 @@ struct LayerState {
   int lines_done = 0;
   int mapped = 0;          // mid rows whose original position is in the survivor map
 };
+
+}  // namespace
+
+// ---- decode_step_static: the split partials live in device memory the library itself holds
+// (a file-scope array), for callers that can neither allocate device memory nor hand over a
+// workspace.  Every GPU the library runs on holds its own copy of the array at its own address
+// until the process ends; the address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char static_scratch[kStaticScratchBytes];
+
+namespace {
+
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of static_scratch (never the array's name: in host code
+// that is only a stand-in for the symbol).  *ptr is null on failure.
+hipError_t static_scratch_ptr(void** ptr) {
+  *ptr = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+    if (e != hipSuccess) return e;
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = p;
+  }
+  *ptr = g_static_ptr[dev];
+  return hipSuccess;
+}
 
 }  // namespace
 
@@ -616,6 +652,71 @@ int kv_free(linear_kv_t* kv) {
   return LINEAR_OK;
 }
 
+int linear_static_scratch_bytes(size_t* bytes) {
+  if (!bytes) return LINEAR_ENULL;
+  void* base = nullptr;
+  const hipError_t e = static_scratch_ptr(&base);
+  if (e != hipSuccess) return hip_fail(e);
+  *bytes = kStaticScratchBytes;
+  return LINEAR_OK;
+}
+
+int decode_step_static(int32_t dtype, int32_t head_dim, int32_t n_pairs, int32_t cached_keys,
+                       int32_t cache_pitch, void* k_cache, void* v_cache, const void* q, const void* k,
+                       const void* v, float scale, int32_t n_split, void* out, void* stream) {
+  if (!k_cache || !v_cache || !q || !k || !v || !out) return LINEAR_ENULL;
+  if (dtype != LINEAR_F32 && dtype != LINEAR_BF16) return LINEAR_EINVAL;
+  if (head_dim != 64 && head_dim != 128) return LINEAR_EINVAL;
+  if (n_pairs < 1 || n_pairs > (1 << 24) || cached_keys < 0 || cache_pitch <= cached_keys ||
+      cache_pitch > (1 << 20))
+    return LINEAR_EINVAL;
+  if (!(scale >= 0.f) || std::isinf(scale)) return LINEAR_EINVAL;
+  if (n_split < 0 || n_split > linear::kMaxSplit) return LINEAR_EINVAL;
+  if (misaligned(k_cache) || misaligned(v_cache) || misaligned(q) || misaligned(k) || misaligned(v) ||
+      misaligned(out))
+    return LINEAR_EALIGN;
+  Plan plan;
+  if (!make_plan(dtype, head_dim, n_pairs, false, 0, n_split, cached_keys, &plan)) return LINEAR_EINVAL;
+  // split partials: numerators [P, n_split, d], then (max, sum) [P, n_split, 2]
+  const size_t part_o_bytes = align_up((size_t)n_pairs * plan.n_split * head_dim * sizeof(float));
+  const size_t part_ml_bytes = (size_t)n_pairs * plan.n_split * 2 * sizeof(float);
+  if (plan.n_split > 1 && part_o_bytes + part_ml_bytes > kStaticScratchBytes) return LINEAR_ECAPACITY;
+  void* base = nullptr;
+  hipError_t e = static_scratch_ptr(&base);
+  if (e != hipSuccess) return hip_fail(e);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int row_bytes = head_dim * (dtype == LINEAR_BF16 ? 2 : 4);
+  if (cached_keys == 0) {
+    // with an empty cache the step's masked loads touch row 0: give it defined bits
+    e = linear::launch_zero_rows(k_cache, cache_pitch, 1, n_pairs, row_bytes, s);
+    if (e == hipSuccess) e = linear::launch_zero_rows(v_cache, cache_pitch, 1, n_pairs, row_bytes, s);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  linear::DecodeArgs a = {};
+  a.q = q;
+  a.k_new = k;
+  a.v_new = v;
+  a.kc = k_cache;
+  a.vc = v_cache;
+  a.out = static_cast<float*>(out);
+  a.part_o = reinterpret_cast<float*>(base);
+  a.part_ml = reinterpret_cast<float*>(static_cast<char*>(base) + part_o_bytes);
+  a.n_pairs = n_pairs;
+  a.t = cached_keys + 1;
+  a.t_max = cache_pitch;
+  a.n_split = plan.n_split;
+  a.rows_per_split = plan.rows_per_split;
+  a.n_waves = plan.n_waves;
+  a.new_wave = plan.new_wave;
+  a.depth = plan.depth;
+  a.max_split = plan.n_split;
+  const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)head_dim);
+  a.scale_log2e = sc * 1.4426950408889634f;
+  e = linear::launch_decode(a, dtype, head_dim, s);
+  if (e != hipSuccess) return hip_fail(e);
+  return LINEAR_OK;
+}
+
 const char* linear_strerror(int code) {
   switch (code) {
     case LINEAR_OK: return "ok";
@@ -624,6 +725,7 @@ const char* linear_strerror(int code) {
     case LINEAR_ENULL: return "required pointer is NULL";
     case LINEAR_EALIGN: return "device pointer is not 16-byte aligned";
     case LINEAR_EHIP: return "HIP call failed";
+    case LINEAR_ECAPACITY: return "the step's split partials exceed the library's static scratch";
     default: return "unknown error";
   }
 }

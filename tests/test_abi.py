@@ -98,6 +98,26 @@ def test_null_and_alignment_errors_without_touching_the_gpu():
     assert L.linear_strerror(-99).decode() == "unknown error"
 
 
+def test_static_step_argument_errors_without_touching_the_gpu():
+    """decode_step_static checks its arguments and the capacity of the library's own scratch
+    array before any device call."""
+    L = binding.lib()
+    ok = dict(dtype=1, d=128, P=8, T=100, pitch=128)
+
+    def call(dtype=1, d=128, P=8, T=100, pitch=128, kc=256, vc=256, q=256, k=256, v=256, scale=0.0, ns=0, out=256):
+        return L.decode_step_static(dtype, d, P, T, pitch, kc, vc, q, k, v, scale, ns, out, None)
+
+    assert call(kc=None) == binding.LINEAR_ENULL and call(out=None) == binding.LINEAR_ENULL
+    assert call(q=264) == binding.LINEAR_EALIGN
+    for bad in (dict(dtype=2), dict(d=96), dict(P=0), dict(T=-1), dict(pitch=100), dict(scale=-1.0),
+                dict(scale=float("inf")), dict(ns=65), dict(ns=-1), dict(T=2_000_000, pitch=2_000_001)):
+        assert call(**bad) == binding.LINEAR_EINVAL, bad
+    # 1024 pairs x 64 workgroups x (128 + 2) floats = 34 MB of partials: more than the array holds
+    assert call(P=1024, T=30000, pitch=30001, ns=64) == binding.LINEAR_ECAPACITY
+    assert "static scratch" in L.linear_strerror(binding.LINEAR_ECAPACITY).decode()
+    assert L.linear_static_scratch_bytes(None) == binding.LINEAR_ENULL
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "liblinear_kv.so"))
