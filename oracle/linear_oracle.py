@@ -28,7 +28,13 @@ mid; score_mode 2 is the paper's "AttAcc" ablation (Sec. 4.4, Table 6: selection
 accumulated attention inside the same pipeline), read the way it describes H2O
 (Sec. 4.2: "accumulated attention"): every cached token carries the sum of the
 decode-time probabilities it has received from every query since it was appended,
-its own included, the sum is never reset and travels with the token; the first
+its own included, the sum is never reset and travels with the token; score_mode 3
+is random eviction (the paper's Random baseline, Sec. 4.2, Table 3) restricted to
+this pipeline's mid region: a candidate's score is a 24-bit integer hash of (seed,
+layer, sequence, head, line, original position), so the n evicted tokens are a
+reproducible pseudo-random draw that both implementations can compute bit for bit
+(the paper's own Random also discards anchor and recent-line tokens, i.e. evicts
+outside the partition; that variant is not this pipeline and is not built); the first
 eviction happens at the end of line B/n, none after the last line;
 BottomK breaks ties by evicting the older (smaller original position) token.
 
@@ -85,6 +91,31 @@ def boundary_gap(S: np.ndarray, k: int) -> float:
     return float((s[k] - s[k - 1]) / s[k]) if s[k] > 0 else 0.0
 
 
+M32 = 0xFFFFFFFF
+
+
+def mix32(x: int) -> int:
+    """A 32-bit integer finaliser (two xorshift-multiply rounds and a closing xorshift,
+    the published "lowbias32" constants): a bijection of the 32-bit integers."""
+    x &= M32
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & M32
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & M32
+    x ^= x >> 16
+    return x
+
+
+def random_key(seed: int, layer: int, sequence: int, head: int, line: int, position: int) -> int:
+    """score_mode 3: the counter-based pseudo-random score of one candidate at one end of
+    line.  The counters are absorbed one by one (add, then mix); the top 24 bits of the
+    result are the score, so that it is exactly representable in single precision."""
+    h = mix32((seed & M32) ^ 0x9E3779B9)
+    for x in (layer, sequence, head, line, position):
+        h = mix32((h + x) & M32)
+    return h >> 8
+
+
 class CacheSlice:
     """The visual KV cache of one (layer, sequence, head) under LineAR.
 
@@ -94,7 +125,7 @@ class CacheSlice:
     """
 
     def __init__(self, K_cond, V_cond, *, line_len, n_lines, budget, n_init,
-                 n_recent_lines, scale=None, score_mode=0):
+                 n_recent_lines, scale=None, score_mode=0, seed=0, layer=0, sequence=0, head=0):
         K_cond = np.asarray(K_cond, F)
         V_cond = np.asarray(V_cond, F)
         self.C, self.d = K_cond.shape
@@ -103,6 +134,8 @@ class CacheSlice:
         self.N_init, self.r = int(n_init), int(n_recent_lines)
         self.scale = 1.0 / math.sqrt(self.d) if scale is None else float(scale)
         self.score_mode = int(score_mode)
+        # score_mode 3 only: the slice's identity, which seeds its random draws
+        self.seed, self.layer, self.sequence, self.head = int(seed), int(layer), int(sequence), int(head)
         if self.B % self.n or not (self.n <= self.B <= self.N):
             raise ValueError("budget must be a multiple of the line length within [n, N]")
         self.compresses = self.B < self.N
@@ -178,6 +211,9 @@ class CacheSlice:
             return saliency(np.stack(self.guide_q), np.stack(self.K[lo:hi]), self.scale)
         if self.score_mode == 2:
             return np.asarray(self.acc[lo:hi], dtype=F)
+        if self.score_mode == 3:
+            return np.asarray([random_key(self.seed, self.layer, self.sequence, self.head, self.line, p)
+                               for p in self.pos[lo:hi]], dtype=F)
         return np.stack(self.guide_p).sum(axis=0) / len(self.guide_p)
 
     def end_of_line(self, force_evict_positions=None) -> dict | None:

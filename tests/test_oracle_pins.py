@@ -340,6 +340,130 @@ def pin_score_mode_2(o):
         np.testing.assert_allclose(sum(received.values()), w.n_visual, rtol=1e-12)
 
 
+def _unmix32(y):
+    """Inverse of the published 32-bit finaliser, built from the modular inverses of its two
+    multipliers and the usual inversion of an xorshift (not a retyping of the forward map)."""
+    M = 0xFFFFFFFF
+
+    def unshift(v, s):
+        x = v
+        for _ in range(32 // s + 1):
+            x = v ^ (x >> s)
+        return x
+
+    y = unshift(y, 16)
+    y = (y * pow(0x846CA68B, -1, 1 << 32)) & M
+    y = unshift(y, 15)
+    y = (y * pow(0x7FEB352D, -1, 1 << 32)) & M
+    return unshift(y, 16)
+
+
+def pin_random_hash(o):
+    """The integer hash behind score_mode 3: a bijection of the 32-bit integers with the published
+    constants (checked through its inverse), good avalanche, keys of 24 bits that single
+    precision holds exactly, every counter matters, and keys are uniform."""
+    rng = np.random.default_rng(5)
+    xs = [0, 1, 2, 0xFFFFFFFF, 0x80000000] + [int(v) for v in rng.integers(0, 1 << 32, 2000)]
+    assert o.mix32(0) == 0                                       # xorshifts and products of zero
+    for x in xs:
+        y = o.mix32(x)
+        assert 0 <= y < (1 << 32) and _unmix32(y) == x
+    flips = [bin(o.mix32(x) ^ o.mix32(x ^ (1 << b))).count("1") for x in xs[5:305] for b in range(32)]
+    assert 15.0 < np.mean(flips) < 17.0                          # one input bit flips about half the output
+    base = dict(seed=7, layer=3, sequence=5, head=2, line=9, position=77)
+    keys = []
+    for s in range(4000):
+        k = o.random_key(**dict(base, seed=s))
+        assert 0 <= k < (1 << 24) and float(np.float32(k)) == k
+        keys.append(k)
+    u = np.array(keys) / float(1 << 24)
+    assert abs(u.mean() - 0.5) < 0.02 and abs(u.var() - 1 / 12) < 0.01
+    hist = np.histogram(u, bins=8, range=(0, 1))[0]
+    assert hist.min() > 400 and hist.max() < 600                 # 500 expected per bin
+    k0 = o.random_key(**base)
+    for name in base:                                            # every counter enters the key
+        same = sum(o.random_key(**dict(base, **{name: base[name] + dv})) == k0 for dv in range(1, 200))
+        assert same <= 1, name
+    assert o.random_key(**base) == k0                            # and nothing else does
+
+
+def pin_score_mode_3(o):
+    """score_mode 3 (random eviction inside the pipeline): the evicted tokens are the n smallest
+    keys (brute-force sort), come from the mid region only, do not depend on the data, are
+    reproducible from the slice's identity, differ between heads, lines and seeds, and over many
+    seeds every candidate slot is evicted equally often."""
+    w = synth.shrink(synth.TINY_C, n_heads=1)
+    kc, vc, Q, K, V = slice_inputs(w)
+    n, C, r = w.line_len, w.n_cond, w.n_recent_lines
+
+    def run(data_sign=1.0, **ident):
+        sl = o.CacheSlice(kc, vc, score_mode=3, **ident, **cfg_of(w))
+        recs = []
+        for i in range(1, w.n_visual + 1):
+            sl.step(data_sign * Q[i - 1], K[i - 1], V[i - 1] * data_sign)
+            if i % n == 0:
+                rec = sl.end_of_line()
+                if rec is not None:
+                    recs.append(rec)
+                    S = rec["scores"]
+                    assert S.shape == (w.budget - w.n_init - r * n,)
+                    assert np.all(S == np.floor(S)) and S.min() >= 0 and S.max() < (1 << 24)
+                    order = np.argsort(S, kind="stable")[:n]
+                    assert sorted(np.array(rec["mid_positions"])[order].tolist()) == rec["evicted_positions"]
+                    assert all(C + w.n_init <= p < C + i - r * n for p in rec["evicted_positions"])
+                    assert set(range(C + w.n_init)) <= set(sl.pos) and set(range(C + i - r * n, C + i)) <= set(sl.pos)
+        assert len(recs) == w.n_lines - w.budget // n
+        return recs
+
+    a = run(seed=11, layer=1, sequence=2, head=3)
+    b = run(data_sign=-1.0, seed=11, layer=1, sequence=2, head=3)
+    assert [x["evicted_positions"] for x in a] == [x["evicted_positions"] for x in b]      # data-independent
+    for other in (dict(seed=12, layer=1, sequence=2, head=3), dict(seed=11, layer=0, sequence=2, head=3),
+                  dict(seed=11, layer=1, sequence=0, head=3), dict(seed=11, layer=1, sequence=2, head=0)):
+        c = run(**other)
+        assert [x["evicted_positions"] for x in a] != [x["evicted_positions"] for x in c]
+    # a token that stays in mid gets a new key on every line
+    first, second = a[0], a[1]
+    common = set(first["mid_positions"]) & set(second["mid_positions"])
+    assert common
+    k1 = dict(zip(first["mid_positions"], first["scores"]))
+    k2 = dict(zip(second["mid_positions"], second["scores"]))
+    assert sum(k1[p] == k2[p] for p in common) == 0
+    # a key belongs to the token (its original position), not to the slot it happens to sit in:
+    # with a shorter anchor the same tokens sit in other slots after the first compaction, and
+    # still draw the same keys on the same line
+    w2 = synth.shrink(synth.Workload("tiny-c4", 1, 1, 4, 64, 8, 8, 8, 32, 4, 1, "f32", 1), n_heads=1)
+    sl2 = o.CacheSlice(kc, vc, score_mode=3, seed=11, layer=1, sequence=2, head=3, **cfg_of(w2))
+    recs2 = []
+    for i in range(1, w2.n_visual + 1):
+        sl2.step(Q[i - 1], K[i - 1], V[i - 1])
+        if i % n == 0:
+            rec = sl2.end_of_line()
+            if rec is not None:
+                recs2.append(rec)
+    shared = 0
+    for ra, rb in zip(a[1:], recs2[1:]):
+        assert ra["line"] == rb["line"]
+        kb = dict(zip(rb["mid_positions"], rb["scores"]))
+        for p_, k_ in zip(ra["mid_positions"], ra["scores"]):
+            if p_ in kb:
+                shared += 1
+                assert kb[p_] == k_
+    assert shared > 10
+    # uniform over the candidate slots: first eviction of 300 seeds, 16 candidates, 8 evicted each
+    counts = np.zeros(w.budget - w.n_init - r * n)
+    for s in range(300):
+        sl = o.CacheSlice(kc, vc, score_mode=3, seed=s, **cfg_of(w))
+        for i in range(w.budget):
+            sl.step(Q[i], K[i], V[i])
+            if sl.pending_eol and i + 1 < w.budget:
+                sl.end_of_line()
+        rec = sl.end_of_line()
+        for p in rec["evicted_positions"]:
+            counts[rec["mid_positions"].index(p)] += 1
+    assert counts.sum() == 300 * n and counts.min() > 110 and counts.max() < 190    # 150 expected
+
+
 def pin_table4_budgets(o):
     """B = rho N as printed in Table 4, and n | B for the line lengths used
     (24 for N = 576; 49 = 48 + one end-of-line token for N = 2352)."""
@@ -435,6 +559,16 @@ MUTANTS = [
      "        self.acc.append(0.0)\n        if self.score_mode == 2:\n            for j in range(len(self.acc) - 1):"),
     ("mode 2 accumulators not compacted", "        self.acc = [self.acc[j] for j in keep]\n", "        self.acc = self.acc[:len(keep)]\n"),
     ("mode 2 accumulates logits", "                self.acc[j] += float(p[j])", "                self.acc[j] += float(logits[j])"),
+    ("random key ignores the line", "for x in (layer, sequence, head, line, position):",
+     "for x in (layer, sequence, head, 0, position):"),
+    ("random key ignores the head", "for x in (layer, sequence, head, line, position):",
+     "for x in (layer, sequence, 0, line, position):"),
+    ("random key ignores the seed", "h = mix32((seed & M32) ^ 0x9E3779B9)", "h = mix32(0x9E3779B9)"),
+    ("random key keeps 32 bits", "    return h >> 8", "    return h"),
+    ("hash multiplier mistyped", "x = (x * 0x846CA68B) & M32", "x = (x * 0x846CA68D) & M32"),
+    ("hash shift mistyped", "    x ^= x >> 15\n", "    x ^= x >> 13\n"),
+    ("random mode scores cache slots instead of tokens", "for p in self.pos[lo:hi]], dtype=F)",
+     "for p in range(lo, hi)], dtype=F)"),
     ("gap uses wrong order statistics", "return float((s[k] - s[k - 1]) / s[k])",
      "return float((s[k + 1] - s[k]) / s[k + 1])"),
 ]
