@@ -168,8 +168,10 @@ LINEAR_API int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, in
  * LINEAR_ESTATE if the layer's current line does not evict. */
 LINEAR_API int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void* stream);
 
-/* Export the retained cache of one layer in canonical order (conditional tokens, then
- * visual tokens in ascending original position).
+/* Export the retained cache of one layer (Sec. 3.3: what Eq. 5-6 leave after the evictions so
+ * far -- conditional tokens, anchor, the mid tokens that survived, the recent lines -- plus the
+ * line being written) in canonical order: conditional tokens, then visual tokens in ascending
+ * original position.
  *   k_out, v_out : DEVICE [Bz, H, len, d] elem (either may be NULL to skip);
  *   pos_out      : DEVICE [Bz, H, len] int32 original positions (cond 0..C-1, visual
  *                  token i at C + i - 1); may be NULL;

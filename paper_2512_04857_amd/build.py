@@ -12,9 +12,7 @@ SOURCES = ["linear_kv.hip", "decode_attn.hip", "evict.hip"]
 # amdgpu-kernarg-preload-count: the leading scalar kernel arguments (the decode kernel's pointers
 # and packed sizes) arrive in SGPRs with the wavefront instead of through a scalar load; measured
 # 0.2-0.4 us per decode launch.  Code objects keep a prologue for firmware without the feature.
-# LINEAR_KERNARG_PRELOAD=0 in the environment builds without it (same results; rocprofv3's
-# counter collection crashed in its own dispatch interception with the preloading code objects,
-# so the counter profiles are taken from such a build).
+# LINEAR_KERNARG_PRELOAD=0 in the environment builds without it (same results, for comparisons).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-result"]
 PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=14"]

@@ -2,14 +2,18 @@
 // BottomK selection (Eq. 10) and in-place gather-compaction (Eq. 5-7), plus the small
 // copy / fill kernels of kv_init and kv_gather.
 //
-// One workgroup per (sequence, head) pair.  The queue holds, for each of the line's n
-// queries, its logits on the mid keys; the workgroup copies it to LDS, takes every row's
-// softmax statistics, and adds the rows up column by column in a fixed order (so the result
-// does not depend on timing).  The candidates are ranked by counting (stable: equal
-// scores rank by age), the n lowest are dropped, the survivors and the r recent lines slide
-// down over the holes.  Rows only ever move to a lower or equal index and keep their order,
-// so processing destination rows in ascending tiles -- load the tile's source rows into
-// registers, barrier, store -- never overwrites a row that is still to be read.
+// One workgroup per (sequence, head) pair (and per layer, when layers share a launch).  The
+// line's guide queue (Eq. 8) holds either the n queries themselves -- then Eq. 9's product
+// Q_guide K_mid^T runs here on the matrix cores, for up to 64 mid keys entirely in the MFMA result
+// registers (saliency_small), else tile by tile into LDS (fill_logits) -- or, for the modes that
+// score decode-time probabilities, every query's logits on the scored keys as the decode step
+// left them, which are copied to LDS.  Either way the workgroup takes every row's softmax
+// statistics and adds the rows up column by column in a fixed order (so the result does not
+// depend on timing).  The candidates are ranked by counting (stable: equal scores rank by age),
+// the n lowest are dropped, the survivors and the r recent lines slide down over the holes.
+// Rows only ever move to a lower or equal index and keep their order, so processing destination
+// rows in ascending tiles -- load the tile's source rows into registers, barrier, store -- never
+// overwrites a row that is still to be read.
 #include "kernels.h"
 #include "lanes.h"
 
