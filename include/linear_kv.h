@@ -50,6 +50,9 @@ extern "C" {
 #define LINEAR_F32 0
 #define LINEAR_BF16 1
 
+#define LINEAR_OUT_F32 0
+#define LINEAR_OUT_ELEM 1
+
 #define LINEAR_QUEUE_AUTO 0
 #define LINEAR_QUEUE_LOGITS 1
 #define LINEAR_QUEUE_QUERIES 2
@@ -75,7 +78,15 @@ typedef struct {
                              2: accumulated attention (the paper's AttAcc ablation, Table 6):
                                 every token behind the anchor carries the sum of the
                                 decode-time probabilities it received from every query since
-                                it was appended, never reset; needs B - N_init <= 7680    */
+                                it was appended, never reset; needs B - N_init <= 7680;
+                             3: random eviction inside the same pipeline (the paper's Random baseline,
+                                Sec. 4.2 / Table 3, restricted to the mid region): a candidate's score is
+                                a 24-bit integer hash of (seed, layer, sequence, head, line, original
+                                position) -- h = mix(seed ^ 0x9e3779b9), then h = mix(h + x) for each of
+                                the five counters in that order, score = h >> 8, where mix(x) is
+                                x ^= x >> 16, x *= 0x7feb352d, x ^= x >> 15, x *= 0x846ca68b, x ^= x >> 16
+                                in 32-bit arithmetic; line counts from 1, positions as kv_gather
+                                reports them.  No guide queue is kept and the decode step scores nothing */
   int32_t guide_queue;    /* what the line's guide queue holds (Eq. 8):
                              LINEAR_QUEUE_QUERIES: the queries themselves, as Eq. 8 prints it;
                                 Eq. 9 is evaluated at the end of the line as the matrix
@@ -83,8 +94,13 @@ typedef struct {
                              LINEAR_QUEUE_LOGITS: every query's logits on the scored keys, taken
                                 from the decode step's own q.k (Eq. 9 then needs no product);
                              LINEAR_QUEUE_AUTO: queries with score_mode 0 (measured faster on
-                                every benchmark workload), logits otherwise                   */
+                                every benchmark workload), logits with score_mode 1 and 2;
+                                score_mode 3 keeps no queue and accepts only this value      */
   float scale;            /* logit scale; 0 selects 1/sqrt(d) (Eq. 2)                 */
+  uint32_t seed;          /* score_mode 3: seed of the random draws; ignored otherwise */
+  int32_t out_dtype;      /* type of decode_step's `out`: LINEAR_OUT_F32 (float), or LINEAR_OUT_ELEM
+                             (the storage type, rounded to nearest even: what the output projection
+                             that follows attention takes as its input)                      */
 } linear_cfg_t;
 
 /* Sizes the caller must allocate (Sec. 3.3: at most C + B pairs per head are cached).
@@ -113,7 +129,9 @@ LINEAR_API int kv_init(const linear_cfg_t* cfg, void* const* k_cache, void* cons
  * end in an eviction): appends (k, v) as visual token i at original position C + i - 1
  * and writes out = Softmax(q K^T * scale) V over every cached key including the new one.
  *   q, k, v : DEVICE [Bz, H, d] elem, already rotated if the model uses RoPE;
- *   out     : DEVICE [Bz, H, d] float.
+ *   out     : DEVICE [Bz, H, d] float (elem with cfg.out_dtype = LINEAR_OUT_ELEM).  Dense row-major,
+ *             so it is at the same time [Bz, H d]: one row per sequence with its heads side by
+ *             side, the left operand of the output projection, with no transpose in between.
  * LINEAR_ESTATE if the layer's line is complete (end_of_line_evict is due) or the image
  * is complete. */
 LINEAR_API int decode_step(linear_kv_t* kv, int32_t layer, const void* q, const void* k, const void* v,
@@ -163,7 +181,8 @@ LINEAR_API int end_of_line_evict_layers(linear_kv_t* kv, int32_t first_layer, in
 
 /* Saliency of the current line so far (Eq. 9): S[j] for the mid candidates, averaged over
  * the n queries of the line (meaningful after the n-th decode_step of an evicting line,
- * before end_of_line_evict); with score_mode 2 the attention accumulated so far.  out: DEVICE [Bz, H, mid] float with
+ * before end_of_line_evict); with score_mode 2 the attention accumulated so far; with
+ * score_mode 3 the candidates' random keys for this line.  out: DEVICE [Bz, H, mid] float with
  * mid = B - N_init - r n; *mid_out (HOST, may be NULL) receives mid.
  * LINEAR_ESTATE if the layer's current line does not evict. */
 LINEAR_API int kv_scores(linear_kv_t* kv, int32_t layer, float* out, int32_t* mid_out, void* stream);

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "liblinear_kv.so")
 LINEAR_OK, LINEAR_EINVAL, LINEAR_ESTATE, LINEAR_ENULL, LINEAR_EALIGN, LINEAR_EHIP, LINEAR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
 LINEAR_F32, LINEAR_BF16 = 0, 1
 LINEAR_QUEUE_AUTO, LINEAR_QUEUE_LOGITS, LINEAR_QUEUE_QUERIES = 0, 1, 2
+LINEAR_OUT_F32, LINEAR_OUT_ELEM = 0, 1
 
 EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_layers",
            "decode_step_rope", "decode_step_rope_layers",
@@ -27,7 +28,7 @@ EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_laye
 class LinearCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "batch", "n_heads", "head_dim", "n_cond", "line_len", "n_lines", "budget",
-        "n_init", "n_recent_lines", "dtype", "score_mode", "guide_queue")] + [("scale", C.c_float)]
+        "n_init", "n_recent_lines", "dtype", "score_mode", "guide_queue")] + [("scale", C.c_float), ("seed", C.c_uint32), ("out_dtype", C.c_int32)]
 
 
 class LinearError(RuntimeError):
@@ -86,17 +87,17 @@ def _check(code: int, what: str) -> None:
 
 
 def make_cfg(*, n_layers, batch, n_heads, head_dim, n_cond, line_len, n_lines, budget, n_init,
-             n_recent_lines, dtype, score_mode=0, guide_queue=0, scale=0.0) -> LinearCfg:
+             n_recent_lines, dtype, score_mode=0, guide_queue=0, scale=0.0, seed=0, out_dtype=0) -> LinearCfg:
     dt = {"f32": LINEAR_F32, "bf16": LINEAR_BF16}.get(dtype, dtype)
     return LinearCfg(n_layers, batch, n_heads, head_dim, n_cond, line_len, n_lines, budget, n_init,
-                     n_recent_lines, dt, score_mode, guide_queue, scale)
+                     n_recent_lines, dt, score_mode, guide_queue, scale, seed, out_dtype)
 
 
-def cfg_from_workload(w, score_mode=0, guide_queue=0, scale=0.0) -> LinearCfg:
+def cfg_from_workload(w, score_mode=0, guide_queue=0, scale=0.0, seed=0, out_dtype=0) -> LinearCfg:
     return make_cfg(n_layers=w.n_layers, batch=w.batch, n_heads=w.n_heads, head_dim=w.head_dim,
                     n_cond=w.n_cond, line_len=w.line_len, n_lines=w.n_lines, budget=w.budget,
                     n_init=w.n_init, n_recent_lines=w.n_recent_lines, dtype=w.dtype,
-                    score_mode=score_mode, guide_queue=guide_queue, scale=scale)
+                    score_mode=score_mode, guide_queue=guide_queue, scale=scale, seed=seed, out_dtype=out_dtype)
 
 
 # ------------------------------------------------------------- thin wrappers ---

@@ -45,6 +45,16 @@ __device__ __forceinline__ void store_nt(float* p, float v) { __builtin_nontempo
 __device__ __forceinline__ void store_nt(uint4* p, const uint4& v) {
   __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(p));
 }
+// Element `idx` of the result, in single precision or rounded to bfloat16 (64 adjacent lanes
+// write 256 or 128 contiguous bytes either way).
+__device__ __forceinline__ void store_out(void* out, int bf16, size_t idx, float v) {
+  if (bf16) {
+    const __bf16 b = (__bf16)v;   // round to nearest even
+    __builtin_nontemporal_store(__builtin_bit_cast(unsigned short, b), static_cast<unsigned short*>(out) + idx);
+  } else {
+    store_nt(static_cast<float*>(out) + idx, v);
+  }
+}
 template <bool BF16>
 struct Elems;
 template <>
@@ -352,7 +362,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(
   if (a.n_split == 1) {
     const float inv = 1.0f / l_all;
 #pragma unroll
-    for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
+    for (int c = 0; c < D / 64; ++c) store_out(a.out, a.out_bf16, (size_t)pair * D + c * 64 + lane, o_all[c] * inv);
     if (scoring && a.store_ml) {
       // the row together with the decode softmax's statistics, which only exist now
       for (int j = lane; j < a.guide_row; j += 64) {
@@ -387,7 +397,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const DecodeArgs a) 
   merge_partials<D, 1>(sm_m, sm_l, a.part_o + pbase * D, a.n_split, m_all, l_all, o_all);
   const float inv = 1.0f / l_all;
 #pragma unroll
-  for (int c = 0; c < D / 64; ++c) store_nt(&a.out[(size_t)pair * D + c * 64 + lane], o_all[c] * inv);
+  for (int c = 0; c < D / 64; ++c) store_out(a.out, a.out_bf16, (size_t)pair * D + c * 64 + lane, o_all[c] * inv);
   if (a.mid_n > 0 && a.store_ml && lane == 0) {
     float* qrow = a.guide + (size_t)pair * a.guide_pitch;
     store_nt(&qrow[a.guide_w], m_all);

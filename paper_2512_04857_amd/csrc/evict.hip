@@ -303,6 +303,32 @@ __device__ void block_saliency(const EvictArgs& a, int pair, float* qs_lds, floa
   __syncthreads();
 }
 
+// Mode 3 (random eviction): sc[j] = the 24-bit hash of (seed, layer, sequence, head, line, original
+// position of candidate j) as a float -- exact, so ranking by it is ranking the integers.  The
+// position comes from the survivor map or, behind the mapped candidates, from the index.  Ends
+// with a barrier.
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7feb352du;
+  x ^= x >> 15;
+  x *= 0x846ca68bu;
+  x ^= x >> 16;
+  return x;
+}
+__device__ void random_scores(const EvictArgs& a, int pair, float* sc) {
+  const int32_t* map = a.pos + (size_t)pair * a.pos_pitch;
+  uint32_t h = mix32(a.seed ^ 0x9e3779b9u);
+  h = mix32(h + (uint32_t)a.layer);
+  h = mix32(h + (uint32_t)(pair / a.n_heads));
+  h = mix32(h + (uint32_t)(pair % a.n_heads));
+  h = mix32(h + (uint32_t)a.line);
+  for (int j = threadIdx.x; j < a.mid_n; j += blockDim.x) {
+    const int32_t pos = j < a.pos_mapped ? map[j] : a.pos_base + j - a.pos_mapped;
+    sc[j] = (float)(mix32(h + (uint32_t)pos) >> 8);
+  }
+  __syncthreads();
+}
+
 // Mode 2: adds the pair's accumulators to the line's column sums; sc[0 .. n_cols) becomes the
 // attention each scored slot has received so far, slots beyond n_cols read as zero.  Ends with
 // a barrier.
@@ -442,6 +468,7 @@ __device__ __forceinline__ EvictArgs layer_args(const EvictArgs& a0, const Evict
   if (a.qq) a.qq = static_cast<const char*>(a.qq) + i * ly.qq_stride;
   a.pos += i * ly.pos_stride;
   a.acc += i * ly.acc_stride;
+  a.layer += i;
   return a;
 }
 
@@ -469,7 +496,8 @@ __global__ __launch_bounds__(kBlock) void evict_kernel(const EvictArgs a0, const
     if (tid < 64) select_small(sc, m, a.n_evict, src, nullptr, &sm_first);
     __syncthreads();
   } else {
-    block_saliency<PPR, 2>(a, pair, qs, st, sc);
+    if (a.score_mode == 3) random_scores(a, pair, sc);
+    else block_saliency<PPR, 2>(a, pair, qs, st, sc);
     if (a.score_mode == 2) add_accumulated(a, pair, sc);
     select_survivors(sc, m, a.n_evict, src, nullptr, &sm_first, sm_mask);
     if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
@@ -559,7 +587,8 @@ __global__ __launch_bounds__(BLOCK) void evict_fast_kernel(const EvictArgs a0, c
     if (tid < 64) select_small(sc, m, a.n_evict, src, dstmap, &sm_first);
     __syncthreads();
   } else {
-    block_saliency<PPR, (PIECES > 4 ? 1 : 2)>(a, pair, qs, st, sc);
+    if (a.score_mode == 3) random_scores(a, pair, sc);
+    else block_saliency<PPR, (PIECES > 4 ? 1 : 2)>(a, pair, qs, st, sc);
     if (a.score_mode == 2) add_accumulated(a, pair, sc);
     select_survivors(sc, m, a.n_evict, src, dstmap, &sm_first, sm_mask);
     if (a.score_mode == 2) compact_accumulated(a, pair, sc, src);
@@ -596,6 +625,8 @@ __global__ __launch_bounds__(kBlock) void saliency_kernel(const EvictArgs a, flo
     float* part = st + 2 * a.n_rows;
     if (a.elem_bf16) saliency_small<PPR, true>(a, pair, part, sc);
     else saliency_small<PPR, false>(a, pair, part, sc);
+  } else if (a.score_mode == 3) {
+    random_scores(a, pair, sc);
   } else {
     block_saliency<PPR, 2>(a, pair, qs, st, sc);
     if (a.score_mode == 2) add_accumulated(a, pair, sc);

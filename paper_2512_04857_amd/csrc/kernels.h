@@ -20,7 +20,8 @@ struct DecodeArgs {
                          //   pair angles of the new token's position, then their sines
   void* kc;           // [P, t_max, d] elem
   void* vc;           // [P, t_max, d] elem
-  float* out;         // [P, d]
+  void* out;          // [P, d] float, or bfloat16 when out_bf16 is set
+  int32_t out_bf16;   // the result leaves in bfloat16 (round to nearest even)
   float* part_o;      // [P, max_split, d]   split partial numerators
   float* part_ml;     // [P, max_split, 2]   split partial (max, sum) in log2 units
   float* guide;       // [P, n, guide_row] guide queue of the layer, already advanced to this
@@ -79,6 +80,11 @@ struct EvictArgs {
   int32_t mid_n;     // candidates
   int32_t n_evict;   // n
   int32_t n_tail;    // rows behind mid that slide down (r lines)
+  // score mode 3 (random eviction): what the candidates' keys are hashed from
+  uint32_t seed;
+  int32_t layer;     // layer index (of the launch's first layer: grid.y is added)
+  int32_t line;      // 1-based raster line that ends
+  int32_t n_heads;   // pair = sequence * n_heads + head
 };
 
 // The layers one end-of-line launch covers (grid.y): layer i of the launch uses kc[i], vc[i] and

@@ -42,6 +42,7 @@ struct Derived {
   // scratch layout (byte offsets)
   int guide_w;      // logits per guide-queue row: mid_n, or B - N_init when attention is accumulated
   bool queries;     // the guide queue holds the queries (Eq. 8 as printed), not their logits
+  bool scored;      // a guide queue is kept at all (not with random eviction)
   size_t off_guide, off_qq, off_pos, off_acc, off_part_o, off_part_ml, total;
   size_t guide_layer, pos_layer, acc_layer;   // element strides per layer
   size_t qq_layer;                 // bytes of one layer's query queue [P, n, d] elem
@@ -54,9 +55,11 @@ int derive(const linear_cfg_t& c, Derived* d) {
   if (c.n_layers < 1 || c.batch < 1 || c.n_heads < 1) return LINEAR_EINVAL;
   if (c.head_dim != 64 && c.head_dim != 128) return LINEAR_EINVAL;
   if (c.dtype != LINEAR_F32 && c.dtype != LINEAR_BF16) return LINEAR_EINVAL;
-  if (c.score_mode < 0 || c.score_mode > 2) return LINEAR_EINVAL;
+  if (c.score_mode < 0 || c.score_mode > 3) return LINEAR_EINVAL;
   if (c.guide_queue < LINEAR_QUEUE_AUTO || c.guide_queue > LINEAR_QUEUE_QUERIES) return LINEAR_EINVAL;
   if (c.guide_queue == LINEAR_QUEUE_QUERIES && c.score_mode != 0) return LINEAR_EINVAL;   // the other modes score decode-time probabilities
+  if (c.score_mode == 3 && c.guide_queue != LINEAR_QUEUE_AUTO) return LINEAR_EINVAL;       // random eviction keeps no queue
+  if (c.out_dtype != LINEAR_OUT_F32 && c.out_dtype != LINEAR_OUT_ELEM) return LINEAR_EINVAL;
   if (c.n_cond < 0 || c.line_len < 1 || c.n_lines < 1) return LINEAR_EINVAL;
   if (!(c.scale >= 0.f) || std::isinf(c.scale)) return LINEAR_EINVAL;
   const int64_t N = (int64_t)c.line_len * c.n_lines;
@@ -83,7 +86,8 @@ int derive(const linear_cfg_t& c, Derived* d) {
   d->guide_w = !d->compresses ? 0 : (c.score_mode == 2 ? c.budget - c.n_init : d->mid_n);
   if (d->guide_w > kMaxScored) return LINEAR_EINVAL;
   d->guide_row = (d->guide_w + 2 + 31) / 32 * 32;
-  d->guide_pair = d->compresses ? (size_t)c.line_len * d->guide_row : 0;
+  d->scored = d->compresses && c.score_mode != 3;
+  d->guide_pair = d->scored ? (size_t)c.line_len * d->guide_row : 0;
   d->queries = d->compresses && c.score_mode == 0 && c.guide_queue != LINEAR_QUEUE_LOGITS;
   // With a queue of queries the logits exist only inside the end-of-line kernel (in LDS, or in
   // one layer's worth of this buffer when they do not fit), so the layers share it.
@@ -254,10 +258,10 @@ void fill_line_args(const linear_kv& kv, int layer, int rows, linear::EvictArgs*
   a->pos = reinterpret_cast<int32_t*>(kv.scratch + d.off_pos) + d.pos_layer * layer;
   a->pos_pitch = d.pos_pitch;
   a->pos_mapped = ls.mapped;
-  // candidates behind the mapped ones: before the first eviction every mid row still sits at
-  // its own index; afterwards they are the line that has just left the recent window
-  a->pos_base = ls.mapped == 0 ? d.mid_lo
-                               : c.n_cond + (ls.lines_done - c.n_recent_lines) * c.line_len;
+  // the candidates behind the mapped ones are consecutive tokens that end where the recent
+  // window begins: at the first eviction all of mid (every row still sits at its own index),
+  // afterwards the line that has just left the window
+  a->pos_base = c.n_cond + (ls.lines_done + 1 - c.n_recent_lines) * c.line_len - (d.mid_n - ls.mapped);
   a->guide = reinterpret_cast<const float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
   a->guide_out = reinterpret_cast<float*>(kv.scratch + d.off_guide) + d.guide_layer * layer;
   a->qq = d.queries ? kv.scratch + d.off_qq + d.qq_layer * layer : nullptr;
@@ -275,6 +279,11 @@ void fill_line_args(const linear_kv& kv, int layer, int rows, linear::EvictArgs*
   a->mid_n = d.mid_n;
   a->n_evict = c.line_len;
   a->n_tail = d.n_tail;
+  a->seed = c.seed;
+  a->layer = layer;
+  a->line = ls.lines_done + 1;
+  a->n_heads = c.n_heads;
+  if (c.score_mode == 3) a->n_rows = 0;   // no queue rows: the scores are hashes
   if (c.score_mode == 2) {
     // the line's first query saw (keys cached before the line) + 1 keys; every later one sees
     // one more; the scored ones are those behind the anchor
@@ -388,7 +397,8 @@ int decode_step_impl(linear_kv_t* kv, int32_t layer, const void* q, const void* 
   a.cos_sin = cos_sin;
   a.kc = kv->k_cache[layer];
   a.vc = kv->v_cache[layer];
-  a.out = static_cast<float*>(out);
+  a.out = out;
+  a.out_bf16 = c.out_dtype == LINEAR_OUT_ELEM && c.dtype == LINEAR_BF16;
   a.part_o = reinterpret_cast<float*>(kv->scratch + d.off_part_o);
   a.part_ml = reinterpret_cast<float*>(kv->scratch + d.off_part_ml);
   a.guide = reinterpret_cast<float*>(kv->scratch + d.off_guide) + d.guide_layer * layer +
@@ -400,7 +410,7 @@ int decode_step_impl(linear_kv_t* kv, int32_t layer, const void* q, const void* 
   a.t = c.n_cond + ls.visual_len + 1;
   a.t_max = d.t_max;
   Plan plan;
-  if (!make_plan(c.dtype, c.head_dim, d.pairs, d.compresses && !d.queries, kv->groups_per_wave,
+  if (!make_plan(c.dtype, c.head_dim, d.pairs, d.scored && !d.queries, kv->groups_per_wave,
                  kv->force_split, a.t - 1, &plan))
     return LINEAR_EINVAL;
   a.n_split = plan.n_split;
@@ -417,7 +427,7 @@ int decode_step_impl(linear_kv_t* kv, int32_t layer, const void* q, const void* 
     a.stage_new = 1;
     a.store_ml = 1;
   } else {
-    a.mid_n = line_evicts(*kv, line) ? d.mid_n : 0;
+    a.mid_n = d.scored && line_evicts(*kv, line) ? d.mid_n : 0;   // random eviction scores nothing
     a.stage_new = 0;
     a.store_ml = c.score_mode == 1;
   }
@@ -635,7 +645,7 @@ int linear_plan_shape(const linear_cfg_t* cfg, int32_t cached_keys, int32_t grou
       n_split < 0 || n_split > linear::kMaxSplit)
     return LINEAR_EINVAL;
   Plan p;
-  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, d.compresses && !d.queries, groups_per_wave, n_split,
+  if (!make_plan(cfg->dtype, cfg->head_dim, d.pairs, d.scored && !d.queries, groups_per_wave, n_split,
                  cached_keys, &p))
     return LINEAR_EINVAL;
   shape[0] = p.n_split;
@@ -698,7 +708,7 @@ int decode_step_static(int32_t dtype, int32_t head_dim, int32_t n_pairs, int32_t
   a.v_new = v;
   a.kc = k_cache;
   a.vc = v_cache;
-  a.out = static_cast<float*>(out);
+  a.out = out;
   a.part_o = reinterpret_cast<float*>(base);
   a.part_ml = reinterpret_cast<float*>(static_cast<char*>(base) + part_o_bytes);
   a.n_pairs = n_pairs;

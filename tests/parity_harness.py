@@ -67,12 +67,13 @@ class ParityReport:
 
 def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, groups_per_wave=0, n_split=0, steps=None,
                seed=synth.BASE_SEED, check_scores=True, progress=None, layers_call=False,
-               fused_rope=False) -> ParityReport:
+               fused_rope=False, random_seed=0, out_elem=False) -> ParityReport:
     """Runs workload `w` on the GPU at its full shape and the oracle on `slices`
     ((layer, sequence, head) triples).  Raises AssertionError on disagreement."""
     o = oracle()
     rep = ParityReport()
-    cfg = binding.cfg_from_workload(w, score_mode=score_mode, guide_queue=guide_queue)
+    cfg = binding.cfg_from_workload(w, score_mode=score_mode, guide_queue=guide_queue, seed=random_seed,
+                                    out_dtype=binding.LINEAR_OUT_ELEM if out_elem else binding.LINEAR_OUT_F32)
     cache = binding.LineARCache(cfg, device)
     kc, vc = synth.cond_kv(w, device, seed)
     cache.start_image(kc, vc)
@@ -86,11 +87,18 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, group
     kc_s, vc_s = f64(kc[li, bi, hi]), f64(vc[li, bi, hi])          # [S, C, d]
     okw = dict(line_len=w.line_len, n_lines=w.n_lines, budget=w.budget, n_init=w.n_init,
                n_recent_lines=w.n_recent_lines, score_mode=score_mode)
-    osl = [o.CacheSlice(kc_s[i], vc_s[i], **okw) for i in range(len(slices))]
+    # score mode 3 draws from the slice's identity and the configuration's seed
+    ident = lambda s: dict(seed=random_seed, layer=s[0], sequence=s[1], head=s[2]) if score_mode == 3 else {}
+    osl = [o.CacheSlice(kc_s[i], vc_s[i], **okw, **ident(slices[i])) for i in range(len(slices))]
     layers_sampled = sorted(set(s[0] for s in slices))
 
     n, N = w.line_len, w.n_visual if steps is None else steps
-    out = torch.empty((w.n_layers, w.batch, w.n_heads, w.head_dim), dtype=torch.float32, device=device)
+    # `out` in the storage type (cfg.out_dtype = LINEAR_OUT_ELEM): rounded once, to nearest even, so
+    # it may sit one bf16 unit (2^-8 relative) from the oracle's value on top of the fp32 agreement
+    out_dt = w.torch_dtype if out_elem else torch.float32
+    out_slack = 2.0 ** -8 if out_dt == torch.bfloat16 else 0.0
+    out = torch.empty((w.n_layers, w.batch, w.n_heads, w.head_dim), dtype=out_dt, device=device)
+    ob = out[0].numel() * out.element_size()
     line_q, line_k, line_v, line_o = [], [], [], []
     compresses = w.budget < w.n_visual
     mid_n = w.budget - w.n_init - w.n_recent_lines * n
@@ -103,7 +111,7 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, group
             if layers_call:
                 binding.decode_step_rope_layers(cache.handle, 0, w.n_layers, q_in.data_ptr(), k_in.data_ptr(),
                                                 v.data_ptr(), cs.data_ptr(), out.data_ptr(),
-                                                q[0].numel() * q.element_size(), out[0].numel() * 4,
+                                                q[0].numel() * q.element_size(), ob,
                                                 cache.stream())
             else:
                 for l in range(w.n_layers):
@@ -113,7 +121,7 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, group
             q, k, v = synth.step_qkv(w, step, device, seed)
             if layers_call:     # the multi-layer entry points, as the benchmark uses them
                 binding.decode_step_layers(cache.handle, 0, w.n_layers, q.data_ptr(), k.data_ptr(), v.data_ptr(),
-                                           out.data_ptr(), q[0].numel() * q.element_size(), out[0].numel() * 4,
+                                           out.data_ptr(), q[0].numel() * q.element_size(), ob,
                                            cache.stream())
             else:
                 for l in range(w.n_layers):
@@ -126,14 +134,14 @@ def run_parity(w, slices, *, device="cuda:0", score_mode=0, guide_queue=0, group
             continue
         line = (step + 1) // n
         Q, K, V = f64(torch.stack(line_q)), f64(torch.stack(line_k)), f64(torch.stack(line_v))
-        O = torch.stack(line_o).cpu().to(torch.float64).numpy()
+        O = torch.stack(line_o).to(torch.float32).cpu().to(torch.float64).numpy()
         line_q, line_k, line_v, line_o = [], [], [], []
         for i, sl in enumerate(osl):
             for j in range(n):
                 ref = sl.step(Q[j, i], K[j, i], V[j, i])
                 err = float(np.abs(ref - O[j, i]).max())
                 rep.max_out_err = max(rep.max_out_err, err)
-                assert err <= OUT_TOL and err <= TIGHT_TOL, (
+                assert err <= OUT_TOL and np.all(np.abs(ref - O[j, i]) <= TIGHT_TOL + out_slack * np.abs(ref)), (
                     f"{w.name}: output mismatch {err:.3e} at step {step - n + 1 + j} slice {slices[i]}")
         rep.steps = step + 1
         evicting = compresses and w.budget // n <= line <= w.n_lines - 1

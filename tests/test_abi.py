@@ -54,7 +54,7 @@ def test_workspace_sizes():
 @pytest.mark.parametrize("over", [
     dict(head_dim=96), dict(head_dim=0), dict(budget=100), dict(budget=0), dict(budget=600),
     dict(n_init=49), dict(n_recent_lines=0), dict(n_recent_lines=3), dict(dtype=7),
-    dict(n_layers=0), dict(batch=0), dict(n_cond=-1), dict(line_len=0), dict(score_mode=3), dict(score_mode=-1), dict(guide_queue=3), dict(guide_queue=-1),
+    dict(n_layers=0), dict(batch=0), dict(n_cond=-1), dict(line_len=0), dict(score_mode=4), dict(score_mode=-1), dict(score_mode=3, guide_queue=1), dict(out_dtype=2), dict(out_dtype=-1), dict(guide_queue=3), dict(guide_queue=-1),
     dict(guide_queue=2, score_mode=1), dict(guide_queue=2, score_mode=2),
     dict(scale=-1.0), dict(scale=float("nan")), dict(scale=float("inf")),
     dict(line_len=1, n_lines=100000, budget=50000, n_init=0),     # mid larger than the ranking limit
