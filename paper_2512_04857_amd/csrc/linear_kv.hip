@@ -65,18 +65,19 @@ int derive(const linear_cfg_t& c, Derived* d) {
   const int64_t N = (int64_t)c.line_len * c.n_lines;
   if (c.budget < c.line_len || c.budget > N || c.budget % c.line_len) return LINEAR_EINVAL;
   if (c.n_init < 0 || c.n_recent_lines < 1) return LINEAR_EINVAL;
+  if (c.n_init > c.budget || c.n_recent_lines > c.n_lines) return LINEAR_EINVAL;   // the anchor and the window are parts of the image
   if ((int64_t)c.n_cond + c.budget > (1 << 20)) return LINEAR_EINVAL;
-  if ((int64_t)c.batch * c.n_heads > (1 << 24)) return LINEAR_EINVAL;
+  if ((int64_t)c.batch * c.n_heads > (1 << 24) || c.n_layers > (1 << 16)) return LINEAR_EINVAL;
   d->compresses = c.budget < N;
-  if (d->compresses &&
-      (int64_t)c.n_init + (int64_t)(c.n_recent_lines + 1) * c.line_len > c.budget)
+  const int64_t tail = (int64_t)c.n_recent_lines * c.line_len;   // r n
+  if (d->compresses && (int64_t)c.n_init + tail + c.line_len > c.budget)
     return LINEAR_EINVAL;   // mid must hold at least the n tokens to evict
   d->pairs = c.batch * c.n_heads;
   d->t_max = c.n_cond + c.budget;
   d->elem = c.dtype == LINEAR_BF16 ? 2 : 4;
   d->row_bytes = c.head_dim * d->elem;
   d->mid_lo = c.n_cond + c.n_init;
-  d->n_tail = c.n_recent_lines * c.line_len;
+  d->n_tail = d->compresses ? (int)tail : 0;                     // (a full cache has no regions)
   d->mid_n = d->compresses ? c.budget - c.n_init - d->n_tail : 0;
   if (d->mid_n > kMaxMid || c.line_len > kMaxLine) return LINEAR_EINVAL;
   d->first_line = c.budget / c.line_len;
@@ -99,6 +100,17 @@ int derive(const linear_cfg_t& c, Derived* d) {
   // lines behind).
   d->pos_pitch = d->compresses ? (std::max(1, d->mid_n - c.line_len) + 31) / 32 * 32 : 32;   // whole 128-byte lines
   d->pos_layer = P * (size_t)d->pos_pitch;
+  // Every part is at most 2^24 pairs x 2^25 words x 2^16 layers, which does not fit 64 bits:
+  // a configuration whose scratch would exceed 2^44 bytes is refused before the offsets are formed.
+  {
+    typedef unsigned __int128 u128;
+    const u128 L = (u128)c.n_layers;
+    const u128 total = (u128)P * d->guide_pair * (d->queries ? 1 : L) * 4 + (u128)d->qq_layer * L +
+                       (u128)d->pos_layer * L * 4 + (u128)d->acc_layer * L * 4 +
+                       (u128)P * d->max_split * (c.head_dim + 2) * 4 + 6 * kAlign;
+    const u128 cache = (u128)P * (u128)d->t_max * d->row_bytes;
+    if (total > ((u128)1 << 44) || cache > ((u128)1 << 44)) return LINEAR_EINVAL;
+  }
   size_t off = 0;
   d->off_guide = off;    off = align_up(off + P * d->guide_pair * (d->queries ? 1 : c.n_layers) * sizeof(float));
   d->off_qq = off;       off = align_up(off + d->qq_layer * c.n_layers);
