@@ -287,6 +287,61 @@ class Runner:
         return e
 
 
+def probe(w, device, reps=3):
+    """What the decode launches are measured against, on the same cache buffers and launch
+    pattern (one launch per layer per token, back to back, all layers cycling): a kernel that
+    only reads the K and V rows a decode step reads (no arithmetic, no store), over the whole
+    image's cache-length trajectory and at fixed lengths; and an empty kernel."""
+    import torch
+
+    from paper_2512_04857_amd import binding
+
+    cfg = binding.cfg_from_workload(w)
+    cache = binding.LineARCache(cfg, device)
+    for t in cache.k_cache + cache.v_cache:
+        t.zero_()
+    kp, vp = [t.data_ptr() for t in cache.k_cache], [t.data_ptr() for t in cache.v_cache]
+    L, N, P = w.n_layers, w.n_visual, w.batch * w.n_heads
+    row_bytes = w.head_dim * cache.k_cache[0].element_size()
+    stream = cache.stream()
+
+    def timed(fn):
+        best = None
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return best
+
+    def stream_rows(rows_list):
+        def fn():
+            for rows in rows_list:
+                binding.linear_probe_stream(kp, vp, P, rows, cache.t_max, row_bytes, stream)
+        ms = timed(fn)
+        launches = len(rows_list) * L
+        byts = sum(rows_list) * 2 * P * row_bytes * L
+        return {"us_per_launch": round(ms * 1e3 / launches, 3), "GBs": round(byts / ms / 1e6, 1),
+                "bytes_per_launch": round(byts / launches), "launches": launches}
+
+    image_rows = [w.n_cond + visual_len_at(w, s) - 1 for s in range(N)]
+    image_rows = [max(r, 1) for r in image_rows]
+    mean_rows = max(1, round(sum(image_rows) / N))
+    out = {
+        "workload": w.name,
+        "empty_launch_us": round(timed(lambda: binding.linear_probe_empty(20 * L, P, 64, stream)) * 1e3 / (20 * L), 3),
+        "stream_whole_image": stream_rows(image_rows),
+        "stream_mean_length": dict(rows=mean_rows, **stream_rows([mean_rows] * 48)),
+        "stream_max_length": dict(rows=cache.t_max - 1, **stream_rows([cache.t_max - 1] * 48)),
+    }
+    cache.close()
+    return out
+
+
 def cache_memory(w, score_mode, guide_queue=0):
     """K/V cache and scratch bytes of the compressed and the full-cache handle (Table 4's memory
     column counts the whole model; this is the cache's share of it)."""
@@ -345,12 +400,19 @@ def main():
     ap.add_argument("--no-whole-image", action="store_true",
                     help="time the window only (profiling runs); the printed line then carries no whole-image keys")
     ap.add_argument("--no-table", action="store_true", help="do not measure the other benchmark workloads")
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark line, print what the decode launches are measured against: a "
+                         "read-only streaming kernel over the same rows and launch pattern, an empty kernel, and "
+                         "the decode path's whole image beside them")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one elementwise read+write pass over this many MiB (a traffic yardstick for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     ap.add_argument("--sequences", type=int, default=0,
                     help="override the number of sequences (e.g. 512 = the paper's Table 4 batch of 256 "
                          "with both guidance halves, for the LlamaGen-XL shape)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="override the number of layers (a few layers' caches stay in the last-level cache: a "
+                         "diagnostic of cache-resident speed, not a benchmark figure)")
     ap.add_argument("--budget-lines", type=int, default=0,
                     help="override the budget B, in raster lines (rho sweeps: 6 of 24 lines = 1/4, ...)")
     ap.add_argument("--score-mode", type=int, default=0,
@@ -377,6 +439,9 @@ def main():
     if args.sequences:
         overrides["batch"] = args.sequences
         w = replace(w, batch=args.sequences, name=f"{w.name}-seq{args.sequences}")
+    if args.layers:
+        overrides["n_layers"] = args.layers
+        w = replace(w, n_layers=args.layers, name=f"{w.name}-L{args.layers}")
     if args.budget_lines:
         overrides["budget"] = args.budget_lines * w.line_len
         w = replace(w, budget=args.budget_lines * w.line_len, name=f"{w.name}-b{args.budget_lines}")
@@ -414,6 +479,22 @@ def main():
         del src, dst
     tune = (args.groups_per_wave, args.n_split)
     variant = (args.score_mode, args.guide_queue, args.fused_rope)
+    if args.probe:
+        res = {"probe": probe(w, device)}
+        img = r.run(w, 0, N, args.warmup, *tune, *variant)
+        res["decode_whole_image"] = {"us_per_launch": round(img["decode_us_per_launch"], 3),
+                                     "GBs": round(img["achieved_GBs"], 1),
+                                     "bytes_per_launch": round(img["kv_bytes_per_launch"]),
+                                     "launches": img["decode_launches"]}
+        if not args.skip_full:
+            res["probe_full_cache"] = probe(w.full_cache(), device)
+            imgf = r.run(w.full_cache(), 0, N, args.warmup, *tune)
+            res["decode_whole_image_full_cache"] = {"us_per_launch": round(imgf["decode_us_per_launch"], 3),
+                                                    "GBs": round(imgf["achieved_GBs"], 1),
+                                                    "bytes_per_launch": round(imgf["kv_bytes_per_launch"]),
+                                                    "launches": imgf["decode_launches"]}
+        print(json.dumps(res), flush=True)
+        return 0
     comp = r.run(w, start, steps, args.warmup, *tune, *variant)
     log("compressed, window:", json.dumps(comp))
     full = None if args.skip_full else r.run(w.full_cache(), start, steps, args.warmup, *tune)
@@ -494,7 +575,7 @@ def main():
         out["us_per_step_first_half"] = img["us_per_step_first_half"]
         out["us_per_step_last_half"] = img["us_per_step_last_half"]
         table = {w.name: img}
-        plain = not (args.sequences or args.budget_lines or args.score_mode or args.guide_queue or args.fused_rope
+        plain = not (args.sequences or args.layers or args.budget_lines or args.score_mode or args.guide_queue or args.fused_rope
                      or args.groups_per_wave or args.n_split)
         if not args.no_table and not args.skip_full and plain:
             del r

@@ -21,7 +21,8 @@ LINEAR_OUT_F32, LINEAR_OUT_ELEM = 0, 1
 EXPORTS = ("linear_workspace_bytes", "kv_init", "decode_step", "decode_step_layers",
            "decode_step_rope", "decode_step_rope_layers",
            "end_of_line_evict", "end_of_line_evict_layers", "kv_scores",
-           "decode_step_static", "linear_static_scratch_bytes", "kv_gather", "kv_length", "linear_set_tuning", "linear_plan_shape", "kv_free", "linear_strerror",
+           "decode_step_static", "linear_static_scratch_bytes", "linear_probe_stream", "linear_probe_empty",
+           "kv_gather", "kv_length", "linear_set_tuning", "linear_plan_shape", "kv_free", "linear_strerror",
            "linear_last_hip_error")
 
 
@@ -71,6 +72,8 @@ def lib() -> C.CDLL:
         L.kv_free.argtypes = [vp]
         L.decode_step_static.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, C.c_float, i32, vp, vp]
         L.linear_static_scratch_bytes.argtypes = [C.POINTER(C.c_size_t)]
+        L.linear_probe_stream.argtypes = [C.POINTER(vp), C.POINTER(vp), i32, i32, i32, i32, i32, vp]
+        L.linear_probe_empty.argtypes = [i32, i32, i32, vp]
         L.linear_strerror.argtypes = [C.c_int]
         L.linear_strerror.restype = C.c_char_p
         L.linear_last_hip_error.argtypes = []
@@ -200,6 +203,16 @@ def linear_static_scratch_bytes() -> int:
     n = C.c_size_t()
     _check(lib().linear_static_scratch_bytes(C.byref(n)), "linear_static_scratch_bytes")
     return n.value
+
+
+def linear_probe_stream(k_cache, v_cache, n_pairs: int, rows: int, pitch_rows: int, row_bytes: int,
+                        stream: int = 0) -> None:
+    _check(lib().linear_probe_stream(_ptr_array(k_cache), _ptr_array(v_cache), len(k_cache), n_pairs, rows,
+                                     pitch_rows, row_bytes, stream), "linear_probe_stream")
+
+
+def linear_probe_empty(launches: int, groups: int, threads: int, stream: int = 0) -> None:
+    _check(lib().linear_probe_empty(launches, groups, threads, stream), "linear_probe_empty")
 
 
 def kv_free(kv: int) -> None:

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblinear_kv.so")
-SOURCES = ["linear_kv.hip", "decode_attn.hip", "evict.hip"]
+SOURCES = ["linear_kv.hip", "decode_attn.hip", "evict.hip", "probe.hip"]
 # -packed-fp32-ops off: the compiler must not form v_pk_*_f32 from the float code.
 # amdgpu-kernarg-preload-count: the leading scalar kernel arguments (the decode kernel's pointers
 # and packed sizes) arrive in SGPRs with the wavefront instead of through a scalar load; measured
@@ -22,9 +22,19 @@ def hipcc() -> str:
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
+BENCH = os.path.join(HERE, "linear_bench")   # native driver of the benchmark's launch sequence (counter profiling)
+
+
 def build(verbose: bool = False, extra=()) -> str:
     preload = [] if os.environ.get("LINEAR_KERNARG_PRELOAD", "1") == "0" else PRELOAD
     cmd = [hipcc(), *FLAGS, *preload, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    # the library is found next to the program ($ORIGIN), wherever the tree is copied to
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", os.path.join(CSRC, "linear_bench.hip"), "-L", HERE, "-llinear_kv",
+           "-Wl,-rpath,$ORIGIN", "-o", BENCH]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

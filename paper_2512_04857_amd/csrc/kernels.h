@@ -124,5 +124,10 @@ hipError_t launch_zero_rows(void* dst, int64_t dst_pitch_rows, int32_t rows, int
 hipError_t launch_positions(int32_t* out, const int32_t* map, int32_t map_pitch, int32_t mid_lo,
                             int32_t mapped, int32_t len, int32_t newest, int32_t n_pairs, hipStream_t s);
 hipError_t launch_fill_u32(void* dst, uint32_t value, size_t n_words, hipStream_t s);
+// Reads rows [0, rows) of every pair of `a` and (when not null) `b` and discards them: the plain
+// streaming yardstick of the probe entry points.  `sink` receives nothing in practice.
+hipError_t launch_stream_read(const void* a, const void* b, int64_t n_pairs, int64_t rows, int64_t pitch_rows,
+                              int32_t row_bytes, uint32_t* sink, hipStream_t s);
+hipError_t launch_empty(int32_t groups, int32_t threads, hipStream_t s);
 
 }  // namespace linear

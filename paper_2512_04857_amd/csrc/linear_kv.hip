@@ -674,6 +674,32 @@ int kv_free(linear_kv_t* kv) {
   return LINEAR_OK;
 }
 
+int linear_probe_stream(const void* const* k_cache, const void* const* v_cache, int32_t n_layers, int32_t n_pairs,
+                        int32_t rows, int32_t pitch_rows, int32_t row_bytes, void* stream) {
+  if (!k_cache || !v_cache) return LINEAR_ENULL;
+  if (n_layers < 1 || n_pairs < 1 || rows < 1 || pitch_rows < rows || row_bytes < 16 || row_bytes % 16)
+    return LINEAR_EINVAL;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    if (!k_cache[l] || !v_cache[l]) return LINEAR_ENULL;
+    if (misaligned(k_cache[l]) || misaligned(v_cache[l])) return LINEAR_EALIGN;
+  }
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const hipError_t e = linear::launch_stream_read(k_cache[l], v_cache[l], n_pairs, rows, pitch_rows, row_bytes,
+                                                    nullptr, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return LINEAR_OK;
+}
+
+int linear_probe_empty(int32_t launches, int32_t groups, int32_t threads, void* stream) {
+  if (launches < 0 || groups < 1 || threads < 1 || threads > 1024) return LINEAR_EINVAL;
+  for (int32_t i = 0; i < launches; ++i) {
+    const hipError_t e = linear::launch_empty(groups, threads, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return LINEAR_OK;
+}
+
 int linear_static_scratch_bytes(size_t* bytes) {
   if (!bytes) return LINEAR_ENULL;
   void* base = nullptr;
