@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/linear_kv.h"
+#include "../../include/linear_kv_diag.h"
 
 #define CK(x)                                                                              \
   do {                                                                                     \

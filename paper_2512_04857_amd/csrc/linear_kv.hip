@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/linear_kv.h"
+#include "../../include/linear_kv_diag.h"
 #include "kernels.h"
 
 namespace {

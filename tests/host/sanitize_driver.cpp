@@ -8,6 +8,7 @@
 #include <initializer_list>
 
 #include "linear_kv.h"
+#include "linear_kv_diag.h"
 
 static linear_cfg_t base() {
   linear_cfg_t c = {};

@@ -570,3 +570,40 @@ def test_decode_steps_replayed_from_a_hip_graph():
     for a, b in zip(eager_kept, graph_kept):
         for x, y in zip(a, b):
             assert torch.equal(x, y)
+
+
+def test_table4_batch_of_512_sequences():
+    """The batch of the paper's efficiency table for the N = 576 class-conditional model (256 images,
+    both guidance halves = 512 sequences, 10240 pairs per launch): other launch plans than the
+    64-sequence benchmark; oracle on eight slices spread over the batch."""
+    from dataclasses import replace
+    w = replace(synth.LLAMAGEN_XL, batch=512, name="llamagen-xl-seq512")
+    sl = sampled_slices(w, [0, w.n_layers - 1], [0, 255, 511], [0, 19]) + [(17, 300, 7), (17, 77, 11)]
+    rep = run_parity(w, sl, layers_call=True)
+    say(f"{w.name}: {len(sl)} slices: {rep}")
+    assert rep.steps == w.n_visual and rep.evictions == 20 * len(sl)
+
+
+def test_measurement_aids_run_and_check_their_arguments():
+    """linear_probe_stream / linear_probe_empty only read: a buffer they stream over is unchanged,
+    and bad arguments come back as error codes."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev).manual_seed(3)
+    bufs = [torch.randint(0, 255, (6 * 40 * 256,), dtype=torch.uint8, device=dev, generator=g) for _ in range(4)]
+    before = [b.clone() for b in bufs]
+    kp, vp = [bufs[0].data_ptr(), bufs[1].data_ptr()], [bufs[2].data_ptr(), bufs[3].data_ptr()]
+    binding.linear_probe_stream(kp, vp, 6, 33, 40, 256)
+    binding.linear_probe_stream(kp, vp, 6, 40, 40, 256)
+    binding.linear_probe_empty(3, 6, 64)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(bufs, before))
+    for bad in (dict(rows=41), dict(rows=0), dict(row_bytes=24), dict(n_pairs=0)):
+        kw = dict(n_pairs=6, rows=33, pitch_rows=40, row_bytes=256)
+        kw.update(bad)
+        with pytest.raises(binding.LinearError) as e:
+            binding.linear_probe_stream(kp, vp, **kw)
+        assert e.value.code == binding.LINEAR_EINVAL
+    with pytest.raises(binding.LinearError):
+        binding.linear_probe_empty(1, 0, 64)
+    with pytest.raises(binding.LinearError):
+        binding.linear_probe_empty(1, 1, 2048)
