@@ -135,10 +135,9 @@ def cpu_baseline(w, base_name, overrides, budget_s: float):
         avail = os.cpu_count() or 1
     cores = max(1, min(avail, 16))          # a one-GPU machine grants 16 cores whatever it reports
     n_heads = min(w.n_heads, 8)
-    base = base_name
     t0 = time.time()
     deadline = t0 + budget_s
-    jobs = [(base, overrides, i, n_heads, deadline, 10 ** 6) for i in range(cores)]
+    jobs = [(base_name, overrides, i, n_heads, deadline, 10 ** 6) for i in range(cores)]
     with mp.get_context("fork").Pool(cores) as pool:
         res = pool.map(_oracle_worker, jobs)
     wall = time.time() - t0
