@@ -68,8 +68,8 @@ typedef struct {
   int32_t line_len;       /* n <= 4096                                                */
   int32_t n_lines;        /* h                                                        */
   int32_t budget;         /* B: multiple of n, n <= B <= h n; B == h n never evicts   */
-  int32_t n_init;         /* N_init >= 0 visual anchor tokens                         */
-  int32_t n_recent_lines; /* r >= 1; needs N_init + (r+1) n <= B when B < h n, and the
+  int32_t n_init;         /* N_init visual anchor tokens, 0 <= N_init <= B            */
+  int32_t n_recent_lines; /* r, 1 <= r <= h; needs N_init + (r+1) n <= B when B < h n, and the
                              mid region B - N_init - r n must not exceed 2048 tokens  */
   int32_t dtype;          /* LINEAR_F32 or LINEAR_BF16: q, k, v and both caches       */
   int32_t score_mode;     /* 0: Eq. 9 as printed, softmax over the mid tokens only;
