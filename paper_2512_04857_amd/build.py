@@ -22,6 +22,7 @@ def hipcc() -> str:
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
+PHASE_CLOCK = os.path.join(HERE, "phase_clock")
 BENCH = os.path.join(HERE, "linear_bench")   # native driver of the benchmark's launch sequence (counter profiling)
 
 
@@ -35,6 +36,12 @@ def build(verbose: bool = False, extra=()) -> str:
     cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
            "-packed-fp32-ops", os.path.join(CSRC, "linear_bench.hip"), "-L", HERE, "-llinear_kv",
            "-Wl,-rpath,$ORIGIN", "-o", BENCH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    # the decode kernel with its phase marks turned into wall-clock stamps (a timing program of its own)
+    cmd = [hipcc(), *[f for f in FLAGS if f not in ("-shared", "-fPIC", "-fvisibility=hidden")], *preload,
+           os.path.join(CSRC, "phase_clock.hip"), "-o", PHASE_CLOCK]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -33,6 +33,13 @@
 #include "kernels.h"
 #include "lanes.h"
 
+// Phase stamps: nothing in the library; the instrumented timing program (phase_clock.hip) defines
+// LINEAR_PHASE(i) to record a wall-clock stamp per wavefront at the marked points of the kernel.
+#ifndef LINEAR_PHASE
+#define LINEAR_PHASE(i)
+#define LINEAR_PHASE_AFTER_STORES(i)
+#endif
+
 namespace linear {
 namespace {
 
@@ -212,6 +219,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int seg = lane % LPR, sub = lane / LPR;
   const int pair = blockIdx.x, split = blockIdx.y;
+  LINEAR_PHASE(0);   // wavefront started
   const int r0 = split * rows_per_split;                 // cached rows [r0, r0 + n_rows)
   const int n_rows = min(t - 1, r0 + rows_per_split) - r0;
 
@@ -260,6 +268,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(
   // instead of interleaved (measured faster, 250 -> 245 us/step at LlamaGen-XL); the logits and
   // the exponentials are then computed while the V rows are on their way.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  LINEAR_PHASE(1);   // K rows arrived
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int u = 0; u < U; ++u) vr[u] = *reinterpret_cast<const uint4*>(vbase + off[u]);
@@ -293,6 +302,7 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(
     m = fmaxf(m, s[u]);
   }
   const float c = a.scale_log2e;          // > 0: scaling commutes with the maximum
+  LINEAR_PHASE(2);   // logits computed (V rows requested before them)
   if (scoring) {
     // Eq. 8-9: the logits of the mid keys (log2 units) are staged in LDS: one 4-byte entry per
     // key from a few lanes each would cost a vector-memory instruction per row group, and the
@@ -338,7 +348,9 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(
     if (seg == 0) sm_l[worker] = l;
     if (lane == 0) sm_m[wave] = m_wave;
   }
+  LINEAR_PHASE(3);   // V rows consumed, partial written to LDS
   __syncthreads();
+  LINEAR_PHASE(4);   // every wavefront of the pair is through
   // A query's guide-queue row (Eq. 8) occupies whole, aligned 128-byte lines and a workgroup that
   // holds all the keys writes all of them, padding included, in one coalesced store: lines
   // written in part cost a read-modify-write at the memory (measured: 0.3 us per launch).
@@ -363,6 +375,8 @@ __global__ __launch_bounds__(64 * MaxWaves<U>::value) void decode_attn_kernel(
     const float inv = 1.0f / l_all;
 #pragma unroll
     for (int c = 0; c < D / 64; ++c) store_out(a.out, a.out_bf16, (size_t)pair * D + c * 64 + lane, o_all[c] * inv);
+    LINEAR_PHASE(5);   // merged and result store issued
+    LINEAR_PHASE_AFTER_STORES(6);
     if (scoring && a.store_ml) {
       // the row together with the decode softmax's statistics, which only exist now
       for (int j = lane; j < a.guide_row; j += 64) {
